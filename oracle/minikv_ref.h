@@ -1,0 +1,94 @@
+/*
+ * CPU oracle for MiniKV's decode-step attention over a 2-bit, evicted KV cache.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, single-precision-for-decisions /
+ * double-precision-for-sums C implementation written straight from the paper (Section 3.1.1 and
+ * Section 3.3 for the quantizer and the packing, Algorithm 1 "Decoding" for the residual buffer and
+ * the attention, Appendix A eq. (1) for the attention definition).  Only the tests, the smoke check
+ * and the benchmark's cpu_baseline leg may use it; the GPU library never links or calls it, and this
+ * directory shares no source, header, table or helper with the GPU library.
+ *
+ * Every pointer is a HOST pointer.  fp16 values travel as raw IEEE binary16 bit patterns (uint16_t).
+ *
+ * Storage order of the packed codes (a storage choice; the paper only fixes "16 two-bit codes per
+ * 32-bit word", Section 3.3):
+ *   K: one word = 16 channels of ONE token.  Channel c of token t lives in word  w = c / 16  of that
+ *      token, at bit  16*(c%2) + 2*((c%16)/2)  (even channels fill the low half-word, odd channels
+ *      the high half-word).  The 8 words of a token are laid out in tiles of 128 tokens:
+ *      word index = tile*1024 + ((2*(t%2) + w/4)*64 + (t%128)/2)*4 + w%4,  tile = t/128.
+ *   V: one word = 16 consecutive tokens of ONE channel.  Token t, channel c: block = (t%64)/16,
+ *      bit 16*(t%2) + 2*((t%16)/2); tiles of 64 tokens:  word index = (t/64)*4*D + c*4 + block.
+ *   Scale / zero-point: fp16, K [Tcap/G][D] per unit (token-group major), V [Tcap][D/G] per unit.
+ *
+ * Pins (tests/ with -m "not gpu"): round-trip half-step bound, code 0/3 presence, lossless lattice,
+ * fp64 arg-min brute force with explicit ties, hand-derived packed words, Appendix I size arithmetic,
+ * fp64 exact attention on a separately dequantized cache, softmax rows summing to 1, T=0 and r=0
+ * special cases, uniform-weight case, GQA == replicated MHA, unit permutation.  No function here is
+ * "parity unpinned".
+ */
+#ifndef MINIKV_REF_H
+#define MINIKV_REF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+    int32_t B, Hq, Hkv, D, G, Tcap, Rcap;
+} ref_shape;
+
+typedef struct {
+    uint32_t *Kc;   /* [B*Hkv][Tcap/128][1024] words                       */
+    uint16_t *Ks;   /* [B*Hkv][Tcap/G][D] fp16                             */
+    uint16_t *Kz;   /* [B*Hkv][Tcap/G][D] fp16                             */
+    uint32_t *Vc;   /* [B*Hkv][Tcap/64][D][4] words                        */
+    uint16_t *Vs;   /* [B*Hkv][Tcap][D/G] fp16                             */
+    uint16_t *Vz;   /* [B*Hkv][Tcap][D/G] fp16                             */
+    int32_t  *q_len;/* [B*Hkv] quantized tokens held, multiple of G        */
+    uint16_t *Rk;   /* [B*Hkv][Rcap][D] fp16 residual keys                 */
+    uint16_t *Rv;   /* [B*Hkv][Rcap][D] fp16 residual values               */
+    int32_t  *r_len;/* [B*Hkv] residual tokens held, 0..Rcap               */
+} ref_cache;
+
+/* IEEE binary16 <-> binary32/64, round-to-nearest-even, subnormals kept. */
+float    ref_f16_to_f32(uint16_t h);
+uint16_t ref_f32_to_f16(float f);
+uint16_t ref_f64_to_f16(double x);
+
+/* 0 when the shape obeys: D==128, G in {16,32,64,128}, Tcap%128==0, Tcap>0, Rcap%G==0, Hq%Hkv==0. */
+int ref_check_shape(const ref_shape *s);
+
+/* Section 3.1.1 / 3.3 + Algorithm 1 line 4: quantize n_tok[u] tokens of K and V (rows idx[u][i] of the
+ * source when idx != NULL, else rows 0..n_tok[u]-1) and append them at token offset q_len[u];
+ * q_len[u] += n_tok[u].  K, V: fp16 [B*Hkv][L][D].  Returns 0, or -1 on a rule violation. */
+int kv_quantize_pack_ref(const ref_shape *s, const uint16_t *K, const uint16_t *V, int64_t L,
+                         const int32_t *idx, int64_t idx_stride, const int32_t *n_tok, ref_cache *c);
+
+/* Algorithm 1 line 9: append one token per unit to the residual; a full unit is left unchanged. */
+int kv_append_residual_ref(const ref_shape *s, const uint16_t *k_new, const uint16_t *v_new,
+                           ref_cache *c);
+
+/* Algorithm 1 lines 10-15: every unit whose residual holds exactly Rcap tokens quantizes it,
+ * appends it to the packed cache and empties the residual. */
+int kv_flush_residual_ref(const ref_shape *s, ref_cache *c);
+
+/* Algorithm 1 lines 17-19 with eq. (1)'s scale passed in as sm_scale.
+ * out_f16 [B*Hq][D] (may be NULL), out_f64 [B*Hq][D] un-rounded (may be NULL),
+ * probs [B*Hq][Tcap+Rcap] softmax weights, quantized tokens first then residual (may be NULL). */
+int minikv_decode_attn_ref(const ref_shape *s, const uint16_t *q, const ref_cache *c, float sm_scale,
+                           uint16_t *out_f16, double *out_f64, double *probs);
+
+/* Layout-free views for tests: codes[unit][t][ch] (0..3) and the dequantized values code*s+z. */
+int ref_unpack_codes(const ref_shape *s, const ref_cache *c, int unit, uint8_t *Kcodes, uint8_t *Vcodes);
+int ref_dequant(const ref_shape *s, const ref_cache *c, int unit, double *Khat, double *Vhat);
+
+/* Appendix I: bytes of one packed group of G codes with its fp16 scale and zero-point. */
+size_t ref_group_bytes(int G);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

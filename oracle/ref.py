@@ -1,0 +1,166 @@
+"""ctypes view of the CPU oracle (oracle/minikv_ref.c).  Test infrastructure, not the product.
+
+Everything here takes and returns numpy arrays in host memory; fp16 travels as numpy float16 whose
+buffer is handed to C as raw binary16 bit patterns.  Nothing in this file does arithmetic of the
+method: it allocates buffers and forwards pointers.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+class _Shape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "D", "G", "Tcap", "Rcap")]
+
+
+class _Cache(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("Kc", "Ks", "Kz", "Vc", "Vs", "Vz", "q_len", "Rk", "Rv", "r_len")]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build()
+        _lib = C.CDLL(path)
+        _lib.ref_f16_to_f32.restype = C.c_float
+        _lib.ref_f16_to_f32.argtypes = [C.c_uint16]
+        _lib.ref_f32_to_f16.restype = C.c_uint16
+        _lib.ref_f32_to_f16.argtypes = [C.c_float]
+        _lib.ref_f64_to_f16.restype = C.c_uint16
+        _lib.ref_f64_to_f16.argtypes = [C.c_double]
+        _lib.ref_group_bytes.restype = C.c_size_t
+        _lib.ref_group_bytes.argtypes = [C.c_int]
+        for name in ("ref_check_shape", "kv_quantize_pack_ref", "kv_append_residual_ref",
+                     "kv_flush_residual_ref", "minikv_decode_attn_ref", "ref_unpack_codes", "ref_dequant"):
+            getattr(_lib, name).restype = C.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else C.c_void_p(a.ctypes.data)
+
+
+class RefShape:
+    def __init__(self, B, Hq, Hkv, D, G, Tcap, Rcap):
+        self.B, self.Hq, self.Hkv, self.D, self.G, self.Tcap, self.Rcap = B, Hq, Hkv, D, G, Tcap, Rcap
+
+    @property
+    def units(self):
+        return self.B * self.Hkv
+
+    def c(self):
+        return _Shape(self.B, self.Hq, self.Hkv, self.D, self.G, self.Tcap, self.Rcap)
+
+    def check(self):
+        return lib().ref_check_shape(C.byref(self.c()))
+
+
+class RefCache:
+    """Host buffers of one cache, zero-initialised, in the storage order minikv_ref.h documents."""
+
+    def __init__(self, s: RefShape):
+        U, D, G, T, R = s.units, s.D, s.G, s.Tcap, s.Rcap
+        self.shape = s
+        self.Kc = np.zeros((U, T // 128 * 1024), np.uint32)
+        self.Ks = np.zeros((U, T // G, D), np.float16)
+        self.Kz = np.zeros((U, T // G, D), np.float16)
+        self.Vc = np.zeros((U, T // 64 * 4 * D), np.uint32)
+        self.Vs = np.zeros((U, T, D // G), np.float16)
+        self.Vz = np.zeros((U, T, D // G), np.float16)
+        self.q_len = np.zeros((U,), np.int32)
+        self.Rk = np.zeros((U, max(R, 1), D), np.float16)
+        self.Rv = np.zeros((U, max(R, 1), D), np.float16)
+        self.r_len = np.zeros((U,), np.int32)
+
+    def c(self):
+        return _Cache(*(a.ctypes.data for a in (self.Kc, self.Ks, self.Kz, self.Vc, self.Vs, self.Vz,
+                                                self.q_len, self.Rk, self.Rv, self.r_len)))
+
+
+def _f16(a):
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.float16, a.dtype
+    return a
+
+
+def quantize_pack(cache: RefCache, K, V, n_tok, idx=None):
+    """K, V: float16 [U, L, D]; n_tok int32 [U]; idx int32 [U, stride] or None."""
+    s = cache.shape
+    K, V = _f16(K), _f16(V)
+    L = K.shape[1]
+    n_tok = np.ascontiguousarray(n_tok, np.int32)
+    stride = 0
+    if idx is not None:
+        idx = np.ascontiguousarray(idx, np.int32)
+        stride = idx.shape[1]
+    cc = cache.c()
+    return lib().kv_quantize_pack_ref(C.byref(s.c()), _p(K), _p(V), C.c_int64(L), _p(idx),
+                                      C.c_int64(stride), _p(n_tok), C.byref(cc))
+
+
+def append_residual(cache: RefCache, k_new, v_new):
+    cc = cache.c()
+    return lib().kv_append_residual_ref(C.byref(cache.shape.c()), _p(_f16(k_new)), _p(_f16(v_new)), C.byref(cc))
+
+
+def flush_residual(cache: RefCache):
+    cc = cache.c()
+    return lib().kv_flush_residual_ref(C.byref(cache.shape.c()), C.byref(cc))
+
+
+def decode_attn(cache: RefCache, q, sm_scale, want_f64=False, want_probs=False):
+    """q float16 [B, Hq, D] -> (out float16 [B,Hq,D], out float64 or None, probs or None)."""
+    s = cache.shape
+    q = _f16(q)
+    out16 = np.zeros((s.B, s.Hq, s.D), np.float16)
+    out64 = np.zeros((s.B, s.Hq, s.D), np.float64) if want_f64 else None
+    probs = np.zeros((s.B, s.Hq, s.Tcap + s.Rcap), np.float64) if want_probs else None
+    cc = cache.c()
+    rc = lib().minikv_decode_attn_ref(C.byref(s.c()), _p(q), C.byref(cc), C.c_float(sm_scale),
+                                      _p(out16), _p(out64), _p(probs))
+    if rc:
+        raise RuntimeError("minikv_decode_attn_ref failed: %d" % rc)
+    return out16, out64, probs
+
+
+def unpack_codes(cache: RefCache, unit):
+    s = cache.shape
+    T = int(cache.q_len[unit])
+    kc = np.zeros((max(T, 1), s.D), np.uint8)
+    vc = np.zeros((max(T, 1), s.D), np.uint8)
+    cc = cache.c()
+    rc = lib().ref_unpack_codes(C.byref(s.c()), C.byref(cc), C.c_int(unit), _p(kc), _p(vc))
+    assert rc == 0
+    return kc[:T], vc[:T]
+
+
+def dequant(cache: RefCache, unit):
+    s = cache.shape
+    T = int(cache.q_len[unit])
+    kh = np.zeros((max(T, 1), s.D), np.float64)
+    vh = np.zeros((max(T, 1), s.D), np.float64)
+    cc = cache.c()
+    rc = lib().ref_dequant(C.byref(s.c()), C.byref(cc), C.c_int(unit), _p(kh), _p(vh))
+    assert rc == 0
+    return kh[:T], vh[:T]
+
+
+def group_bytes(G):
+    return int(lib().ref_group_bytes(G))
+
+
+def f32_to_f16_bits(x):
+    return int(lib().ref_f32_to_f16(C.c_float(x)))
+
+
+def f64_to_f16_bits(x):
+    return int(lib().ref_f64_to_f16(C.c_double(x)))
+
+
+def f16_bits_to_f32(h):
+    return float(lib().ref_f16_to_f32(C.c_uint16(h)))
