@@ -1,0 +1,141 @@
+/*
+ * libminikv -- MiniKV decode-step attention over a 2-bit, adaptively evicted KV cache, for AMD MI355X
+ * (gfx950).  C ABI: plain pointers and sizes, no C++ or framework types.
+ *
+ * What the calls compute is taken from the MiniKV paper: the 2-bit asymmetric group quantizer with
+ * fp16 scale and zero-point and 16 codes per 32-bit word (Section 3.1.1, Section 3.3), the fp16
+ * residual buffer that is compressed every n_r steps (Section 3.3, Algorithm 1 lines 9-15) and the
+ * decode attention with dequantization fused into both products (Algorithm 1 lines 17-19), whose
+ * result is softmax(q K^T * sm_scale) V of Appendix A eq. (1) over the compressed cache.
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned; the library never
+ *     allocates, frees or synchronises.  All work is enqueued on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream).  Lengths live in device memory so a decode loop never waits
+ *     for the host.
+ *   - fp16 = IEEE binary16 bit patterns (minikv_f16).  Inputs must be finite.
+ *   - A "unit" is one (batch, KV head): u = b * Hkv + h.  Query head hq reads unit b*Hkv + hq/(Hq/Hkv).
+ *   - Return value: MINIKV_OK (0) or a negative minikv_status; all checks happen on the host before
+ *     anything is launched.  Values held in device memory (lengths, indices) are not validated; the
+ *     kernels clamp lengths to the capacities.
+ *
+ * Shape rules: D == 128; G in {16, 32, 64, 128}; Tcap > 0 and Tcap % 128 == 0; Rcap % G == 0
+ * (Rcap may be 0); Hq % Hkv == 0 and Hq / Hkv <= 8.
+ *
+ * Quantizer (Section 3.1.1 / 3.3).  For a group x_0..x_{G-1}: zero = min (fp16, -0 stored as +0),
+ * scale = fp16_rne((max - min) / 3) with the subtraction and division in binary32,
+ * code_i = clamp(rne((x_i - zero) * (1 / scale)), 0, 3) with each operation rounded to binary32 and
+ * the reciprocal taken of the STORED fp16 scale (scale == 0: all codes 0), x_hat = code*scale + zero.
+ * K groups are G consecutive retained tokens of one channel; V groups are G consecutive channels of one
+ * token.
+ *
+ * Storage order (per unit; a storage choice made for coalesced 128-bit loads, the grouping above is
+ * the paper's):
+ *   Kc  uint32 [Tcap/128][4][64][4]   one word = 16 channels of ONE token: channel c of token t is in
+ *       the token's word w = c/16 at bit 16*(c%2) + 2*((c%16)/2) (even channels in the low half-word,
+ *       odd channels in the high one).  Word index = (t/128)*1024 + ((2*(t%2) + w/4)*64 + (t%128)/2)*4
+ *       + w%4.
+ *   Ks, Kz  fp16 [Tcap/G][D]          scale / zero of token group t/G, channel c.
+ *   Vc  uint32 [Tcap/64][D][4]        one word = 16 consecutive tokens of ONE channel: token t is in
+ *       block (t%64)/16 at bit 16*(t%2) + 2*((t%16)/2).  Word index = (t/64)*4*D + c*4 + (t%64)/16.
+ *   Vs, Vz  fp16 [Tcap][D/G]          scale / zero of token t, channel group c/G.
+ *   Rk, Rv  fp16 [Rcap][D]            residual rows, newest last.
+ *   q_len, r_len  int32 [B*Hkv]       quantized tokens held (multiple of G) / residual rows held.
+ */
+#ifndef MINIKV_H
+#define MINIKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MINIKV_ABI_VERSION 1
+
+typedef uint16_t minikv_f16;
+
+typedef enum {
+    MINIKV_OK = 0,
+    MINIKV_EINVAL = -1,        /* null or misaligned pointer, or a shape rule violated        */
+    MINIKV_EUNSUPPORTED = -2,  /* D != 128, G not in the list, Hq/Hkv > 8                     */
+    MINIKV_EWORKSPACE = -3,    /* workspace smaller than minikv_workspace_bytes()             */
+    MINIKV_ELAUNCH = -4        /* the HIP runtime refused a launch (hipGetLastError != 0)     */
+} minikv_status;
+
+typedef struct minikv_shape {
+    int32_t B, Hq, Hkv, D, G, Tcap, Rcap;
+} minikv_shape;
+
+typedef struct minikv_cache {
+    uint32_t   *Kc;
+    minikv_f16 *Ks, *Kz;
+    uint32_t   *Vc;
+    minikv_f16 *Vs, *Vz;
+    int32_t    *q_len;
+    minikv_f16 *Rk, *Rv;
+    int32_t    *r_len;
+} minikv_cache;
+
+/* Index of a buffer for minikv_buffer_bytes(). */
+typedef enum {
+    MINIKV_BUF_KC = 0, MINIKV_BUF_KS, MINIKV_BUF_KZ, MINIKV_BUF_VC, MINIKV_BUF_VS, MINIKV_BUF_VZ,
+    MINIKV_BUF_QLEN, MINIKV_BUF_RK, MINIKV_BUF_RV, MINIKV_BUF_RLEN
+} minikv_buffer;
+
+int         minikv_abi_version(void);
+const char *minikv_strerror(int status);
+
+/* Host-only helpers.  Bytes the caller must allocate for buffer `which` of a cache of this shape
+ * (0 on an invalid shape), and for the split-K workspace of minikv_decode_attn. */
+size_t minikv_buffer_bytes(const minikv_shape *shape, int which);
+size_t minikv_workspace_bytes(const minikv_shape *shape);
+
+/* Algorithm 1 lines 3-5 (gather the retained tokens, quantize, pack) -- Section 3.1.1 / 3.3.
+ * For every unit u: take n_tok[u] rows of K and V -- rows idx[u*idx_stride + i] (ascending) when idx is
+ * not NULL, else rows 0..n_tok[u]-1 -- quantize them and write them at token offset q_len[u];
+ * then q_len[u] += n_tok[u].
+ *   K, V     fp16 [B*Hkv][L][D], contiguous                 (device, read)
+ *   idx      int32 [B*Hkv][idx_stride] or NULL              (device, read)
+ *   n_tok    int32 [B*Hkv], each a multiple of G, <= L      (device, read)
+ *   max_tok  host-side upper bound of every n_tok[u] (sizes the launch; multiple of G, <= Tcap)
+ * A unit whose q_len[u] + n_tok[u] would exceed Tcap, or whose n_tok is not a positive multiple of G,
+ * is left unchanged. */
+int kv_quantize_pack(const minikv_shape *shape, const minikv_f16 *K, const minikv_f16 *V, int64_t L,
+                     const int32_t *idx, int64_t idx_stride, const int32_t *n_tok, int32_t max_tok,
+                     minikv_cache *cache, void *stream);
+
+/* Algorithm 1 line 9: Rk[u][r_len[u]] = k_new[u], Rv likewise, r_len[u] += 1.
+ *   k_new, v_new  fp16 [B*Hkv][D]                           (device, read)
+ * A unit whose residual is already full (r_len == Rcap) is left unchanged: flush first. */
+int kv_append_residual(const minikv_shape *shape, const minikv_f16 *k_new, const minikv_f16 *v_new,
+                       minikv_cache *cache, void *stream);
+
+/* Algorithm 1 lines 10-15: every unit with r_len[u] == Rcap (and room for Rcap more tokens) quantizes
+ * its residual rows, appends them at q_len[u], then q_len[u] += Rcap and r_len[u] = 0.  Other units
+ * are untouched.  The decision is taken on the device; calling it every step is cheap. */
+int kv_flush_residual(const minikv_shape *shape, minikv_cache *cache, void *stream);
+
+/* Algorithm 1 lines 17-19 / eq. (1):
+ *   out[b][hq] = softmax(sm_scale * q[b][hq] . [K_hat ; Rk]^T) . [V_hat ; Rv]
+ * over the q_len[u] quantized and r_len[u] residual tokens of unit u = b*Hkv + hq/(Hq/Hkv), one softmax
+ * over the concatenation, fp32 accumulation, fp16 result.  A unit with no tokens gives zeros.
+ *   q    fp16 [B][Hq][D]  (device, read)      out  fp16 [B][Hq][D]  (device, written)
+ *   workspace  device scratch of at least minikv_workspace_bytes(shape) bytes, 16-byte aligned; its
+ *              contents need not be initialised and are undefined afterwards.  Two calls that share a
+ *              workspace must be ordered (same stream). */
+int minikv_decode_attn(const minikv_shape *shape, const minikv_f16 *q, const minikv_cache *cache,
+                       float sm_scale, minikv_f16 *out, void *workspace, size_t workspace_bytes,
+                       void *stream);
+
+/* Diagnostics: selects the kernel variant minikv_decode_attn launches (process-wide).
+ *   0 = default (fastest verified), 1 = plain scalar-loop kernel kept for cross-checks,
+ *   others as listed by minikv_strvariant().  Returns MINIKV_EINVAL for an unknown id. */
+int         minikv_set_variant(int variant);
+const char *minikv_strvariant(int variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

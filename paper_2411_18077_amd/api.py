@@ -1,0 +1,150 @@
+"""Thin Python binding of libminikv.so: argument marshalling only.
+
+Every function here has the name and the argument order of its C entry point in include/minikv.h and
+forwards device pointers of torch tensors (torch is used for device memory and streams, nothing else).
+There is no CPU fallback: if the HIP library is missing, loading raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libminikv.so")
+
+BUF_NAMES = ("Kc", "Ks", "Kz", "Vc", "Vs", "Vz", "q_len", "Rk", "Rv", "r_len")
+_BUF_DTYPE = dict(Kc=torch.int32, Vc=torch.int32, q_len=torch.int32, r_len=torch.int32,
+                  Ks=torch.float16, Kz=torch.float16, Vs=torch.float16, Vz=torch.float16,
+                  Rk=torch.float16, Rv=torch.float16)
+
+
+class MinikvShape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "D", "G", "Tcap", "Rcap")]
+
+
+class MinikvCache(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in BUF_NAMES]
+
+
+class MinikvError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, lib().minikv_strerror(status).decode(), status))
+
+
+_lib = None
+
+
+def lib():
+    """Load libminikv.so (built in-tree by `python -m paper_2411_18077_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libminikv.so is not built: run `python -m paper_2411_18077_amd.build` "
+                              "(there is no fallback path)")
+        l = C.CDLL(LIB_PATH)
+        l.minikv_abi_version.restype = C.c_int
+        l.minikv_strerror.restype = C.c_char_p
+        l.minikv_strerror.argtypes = [C.c_int]
+        l.minikv_strvariant.restype = C.c_char_p
+        l.minikv_strvariant.argtypes = [C.c_int]
+        l.minikv_set_variant.restype = C.c_int
+        l.minikv_set_variant.argtypes = [C.c_int]
+        l.minikv_buffer_bytes.restype = C.c_size_t
+        l.minikv_buffer_bytes.argtypes = [C.POINTER(MinikvShape), C.c_int]
+        l.minikv_workspace_bytes.restype = C.c_size_t
+        l.minikv_workspace_bytes.argtypes = [C.POINTER(MinikvShape)]
+        P = C.c_void_p
+        l.kv_quantize_pack.restype = C.c_int
+        l.kv_quantize_pack.argtypes = [C.POINTER(MinikvShape), P, P, C.c_int64, P, C.c_int64, P, C.c_int32,
+                                       C.POINTER(MinikvCache), P]
+        l.kv_append_residual.restype = C.c_int
+        l.kv_append_residual.argtypes = [C.POINTER(MinikvShape), P, P, C.POINTER(MinikvCache), P]
+        l.kv_flush_residual.restype = C.c_int
+        l.kv_flush_residual.argtypes = [C.POINTER(MinikvShape), C.POINTER(MinikvCache), P]
+        l.minikv_decode_attn.restype = C.c_int
+        l.minikv_decode_attn.argtypes = [C.POINTER(MinikvShape), P, C.POINTER(MinikvCache), C.c_float, P, P,
+                                         C.c_size_t, P]
+        _lib = l
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise MinikvError(rc, where)
+
+
+def make_shape(B, Hq, Hkv, D, G, Tcap, Rcap):
+    return MinikvShape(B, Hq, Hkv, D, G, Tcap, Rcap)
+
+
+def buffer_bytes(shape, which):
+    return int(lib().minikv_buffer_bytes(C.byref(shape), which))
+
+
+def workspace_bytes(shape):
+    return int(lib().minikv_workspace_bytes(C.byref(shape)))
+
+
+class Cache:
+    """Caller-owned device buffers of one cache (torch tensors), sized by minikv_buffer_bytes."""
+
+    def __init__(self, shape, device="cuda", fill=None):
+        self.shape = shape
+        self.t = {}
+        for i, name in enumerate(BUF_NAMES):
+            nbytes = buffer_bytes(shape, i)
+            dt = _BUF_DTYPE[name]
+            n = max(nbytes // dt.itemsize, 1)         # Rcap == 0: a 1-element placeholder
+            self.t[name] = torch.zeros(n, dtype=dt, device=device)
+        self.workspace = torch.empty(max(workspace_bytes(shape), 16), dtype=torch.uint8, device=device)
+
+    def __getattr__(self, name):
+        t = self.__dict__.get("t", {})
+        if name in t:
+            return t[name]
+        raise AttributeError(name)
+
+    def c(self):
+        return MinikvCache(*(self.t[n].data_ptr() for n in BUF_NAMES))
+
+    def nbytes(self):
+        return sum(v.numel() * v.element_size() for v in self.t.values())
+
+
+def kv_quantize_pack(shape, K, V, L, idx, idx_stride, n_tok, max_tok, cache, stream=None):
+    cc = cache.c()
+    _check(lib().kv_quantize_pack(C.byref(shape), _ptr(K), _ptr(V), int(L), _ptr(idx), int(idx_stride),
+                                  _ptr(n_tok), int(max_tok), C.byref(cc), _stream(stream)), "kv_quantize_pack")
+
+
+def kv_append_residual(shape, k_new, v_new, cache, stream=None):
+    cc = cache.c()
+    _check(lib().kv_append_residual(C.byref(shape), _ptr(k_new), _ptr(v_new), C.byref(cc), _stream(stream)),
+           "kv_append_residual")
+
+
+def kv_flush_residual(shape, cache, stream=None):
+    cc = cache.c()
+    _check(lib().kv_flush_residual(C.byref(shape), C.byref(cc), _stream(stream)), "kv_flush_residual")
+
+
+def minikv_decode_attn(shape, q, cache, sm_scale, out, workspace=None, stream=None):
+    cc = cache.c()
+    ws = cache.workspace if workspace is None else workspace
+    _check(lib().minikv_decode_attn(C.byref(shape), _ptr(q), C.byref(cc), float(sm_scale), _ptr(out), _ptr(ws),
+                                    ws.numel() * ws.element_size(), _stream(stream)), "minikv_decode_attn")
+
+
+def minikv_set_variant(v):
+    _check(lib().minikv_set_variant(int(v)), "minikv_set_variant")

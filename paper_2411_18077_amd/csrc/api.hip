@@ -1,0 +1,162 @@
+// Host side of libminikv: argument checks, buffer sizes, launch geometry, C entry points.
+#include "common.h"
+
+#include <atomic>
+
+namespace minikv {
+
+static std::atomic<int> g_variant{0};
+
+int validate_shape(const minikv_shape *s)
+{
+    if (!s) return MINIKV_EINVAL;
+    if (s->D != kD) return MINIKV_EUNSUPPORTED;
+    if (!(s->G == 16 || s->G == 32 || s->G == 64 || s->G == 128)) return MINIKV_EUNSUPPORTED;
+    if (s->B <= 0 || s->Hq <= 0 || s->Hkv <= 0 || s->Hq % s->Hkv) return MINIKV_EINVAL;
+    if (s->Hq / s->Hkv > kMaxRep) return MINIKV_EUNSUPPORTED;
+    if (s->Tcap <= 0 || s->Tcap % kKTile) return MINIKV_EINVAL;
+    if (s->Rcap < 0 || s->Rcap % s->G) return MINIKV_EINVAL;
+    if ((int64_t)s->B * s->Hkv > (1 << 22)) return MINIKV_EINVAL;
+    return MINIKV_OK;
+}
+
+DecodeGeom decode_geom(const minikv_shape &s)
+{
+    // Chunk size: enough workgroups to cover the chip several times over, but no smaller than kMinChunk
+    // so that the split-K partials stay a small fraction of the bytes read.
+    const long units = (long)s.B * s.Hkv;
+    int chunk = kMinChunk;
+    while (chunk < 4096 && units * ((s.Tcap + 2 * chunk - 1) / (2 * chunk)) >= 2048) chunk *= 2;
+    DecodeGeom g;
+    g.chunk = chunk;
+    g.nchunk = (s.Tcap + chunk - 1) / chunk;
+    g.rep = s.Hq / s.Hkv;
+    return g;
+}
+
+static bool aligned16(const void *p) { return p && ((uintptr_t)p & 15u) == 0; }
+
+static int validate_cache(const minikv_shape &s, const minikv_cache *c)
+{
+    if (!c) return MINIKV_EINVAL;
+    if (!aligned16(c->Kc) || !aligned16(c->Ks) || !aligned16(c->Kz) || !aligned16(c->Vc) ||
+        !aligned16(c->Vs) || !aligned16(c->Vz) || !c->q_len || !c->r_len)
+        return MINIKV_EINVAL;
+    if (s.Rcap > 0 && (!aligned16(c->Rk) || !aligned16(c->Rv))) return MINIKV_EINVAL;
+    return MINIKV_OK;
+}
+
+}  // namespace minikv
+
+using namespace minikv;
+
+extern "C" {
+
+int minikv_abi_version(void) { return MINIKV_ABI_VERSION; }
+
+const char *minikv_strerror(int status)
+{
+    switch (status) {
+    case MINIKV_OK: return "ok";
+    case MINIKV_EINVAL: return "invalid argument (null or misaligned pointer, or a shape rule violated)";
+    case MINIKV_EUNSUPPORTED: return "unsupported shape (D must be 128, G in {16,32,64,128}, Hq/Hkv <= 8)";
+    case MINIKV_EWORKSPACE: return "workspace too small (see minikv_workspace_bytes)";
+    case MINIKV_ELAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+    }
+}
+
+size_t minikv_buffer_bytes(const minikv_shape *s, int which)
+{
+    if (validate_shape(s) != MINIKV_OK) return 0;
+    const size_t U = (size_t)s->B * s->Hkv;
+    switch (which) {
+    case MINIKV_BUF_KC: return U * kc_words(s->Tcap) * 4;
+    case MINIKV_BUF_KS:
+    case MINIKV_BUF_KZ: return U * (size_t)(s->Tcap / s->G) * kD * 2;
+    case MINIKV_BUF_VC: return U * vc_words(s->Tcap) * 4;
+    case MINIKV_BUF_VS:
+    case MINIKV_BUF_VZ: return U * (size_t)s->Tcap * (kD / s->G) * 2;
+    case MINIKV_BUF_QLEN:
+    case MINIKV_BUF_RLEN: return U * 4;
+    case MINIKV_BUF_RK:
+    case MINIKV_BUF_RV: return U * (size_t)s->Rcap * kD * 2;
+    default: return 0;
+    }
+}
+
+size_t minikv_workspace_bytes(const minikv_shape *s)
+{
+    if (validate_shape(s) != MINIKV_OK) return 0;
+    // sized for the smallest chunk any variant uses, plus the residual chunk
+    const size_t nch = (size_t)(s->Tcap + kMinChunk - 1) / kMinChunk + 1;
+    return (size_t)s->B * s->Hq * nch * kPartialStride * sizeof(float);
+}
+
+int kv_quantize_pack(const minikv_shape *s, const minikv_f16 *K, const minikv_f16 *V, int64_t L,
+                     const int32_t *idx, int64_t idx_stride, const int32_t *n_tok, int32_t max_tok,
+                     minikv_cache *c, void *stream)
+{
+    int rc = validate_shape(s);
+    if (rc) return rc;
+    if ((rc = validate_cache(*s, c))) return rc;
+    if (!aligned16(K) || !aligned16(V) || !n_tok || L <= 0) return MINIKV_EINVAL;
+    if (max_tok < 0 || max_tok % s->G || max_tok > s->Tcap || max_tok > L) return MINIKV_EINVAL;
+    if (idx && idx_stride < max_tok) return MINIKV_EINVAL;
+    if (max_tok == 0) return MINIKV_OK;
+    return launch_quantize(*s, K, V, L, idx, idx_stride, n_tok, max_tok, *c, false, (hipStream_t)stream);
+}
+
+int kv_flush_residual(const minikv_shape *s, minikv_cache *c, void *stream)
+{
+    int rc = validate_shape(s);
+    if (rc) return rc;
+    if ((rc = validate_cache(*s, c))) return rc;
+    if (s->Rcap == 0) return MINIKV_OK;
+    if (s->Rcap > s->Tcap) return MINIKV_EINVAL;
+    return launch_quantize(*s, c->Rk, c->Rv, s->Rcap, nullptr, 0, c->r_len, s->Rcap, *c, true,
+                           (hipStream_t)stream);
+}
+
+int kv_append_residual(const minikv_shape *s, const minikv_f16 *k_new, const minikv_f16 *v_new,
+                       minikv_cache *c, void *stream)
+{
+    int rc = validate_shape(s);
+    if (rc) return rc;
+    if ((rc = validate_cache(*s, c))) return rc;
+    if (!aligned16(k_new) || !aligned16(v_new)) return MINIKV_EINVAL;
+    if (s->Rcap == 0) return MINIKV_EINVAL;
+    return launch_append(*s, k_new, v_new, *c, (hipStream_t)stream);
+}
+
+int minikv_decode_attn(const minikv_shape *s, const minikv_f16 *q, const minikv_cache *c, float sm_scale,
+                       minikv_f16 *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = validate_shape(s);
+    if (rc) return rc;
+    if ((rc = validate_cache(*s, c))) return rc;
+    if (!aligned16(q) || !aligned16(out) || !aligned16(workspace)) return MINIKV_EINVAL;
+    if (!(sm_scale == sm_scale) || sm_scale - sm_scale != 0.0f) return MINIKV_EINVAL;   // NaN / Inf
+    if (workspace_bytes < minikv_workspace_bytes(s)) return MINIKV_EWORKSPACE;
+    return launch_decode(*s, q, *c, sm_scale, out, (float *)workspace, g_variant.load(), (hipStream_t)stream);
+}
+
+int minikv_set_variant(int variant)
+{
+    if (variant < 0 || variant > 3) return MINIKV_EINVAL;
+    g_variant.store(variant);
+    return MINIKV_OK;
+}
+
+const char *minikv_strvariant(int variant)
+{
+    switch (variant) {
+    case 0: return "default";
+    case 1: return "scalar: plain per-token loops, fp32 FMA (cross-check kernel)";
+    case 2: return "wave-tiled, packed-fp16 dot products on the vector ALU";
+    case 3: return "wave-tiled, 4x4x4 fp16 matrix-core blocks for the head x channel products";
+    default: return "unknown";
+    }
+}
+
+}  // extern "C"

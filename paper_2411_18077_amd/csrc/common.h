@@ -1,0 +1,59 @@
+// Internal declarations shared by the translation units of libminikv (GPU library only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "minikv.h"
+
+namespace minikv {
+
+constexpr int kD = 128;            // head dimension (the only one supported)
+constexpr int kKTile = 128;        // tokens per K code tile (1024 words)
+constexpr int kVTile = 64;         // tokens per V code tile (4*D words)
+constexpr int kPartialStride = 132;  // floats per split-K partial: m, l, 2 pad, o[128]
+constexpr int kMinChunk = 512;     // smallest token chunk one workgroup of the decode kernel takes
+constexpr int kMaxRep = 8;         // most query heads per KV head
+
+// per-unit element counts
+__host__ __device__ inline size_t kc_words(int Tcap) { return (size_t)Tcap / kKTile * 1024; }
+__host__ __device__ inline size_t vc_words(int Tcap) { return (size_t)Tcap / kVTile * 4 * kD; }
+
+// Word index (inside one unit's Kc) of word w (0..7) of token t.
+__host__ __device__ inline uint32_t k_word_index(int t, int w)
+{
+    int tile = t >> 7, tau = t & 127;
+    return (uint32_t)tile * 1024u + (uint32_t)(((2 * (tau & 1) + (w >> 2)) * 64 + (tau >> 1)) * 4 + (w & 3));
+}
+// Bit position of channel c inside its K word.
+__host__ __device__ inline int k_bit(int c) { return 16 * (c & 1) + 2 * ((c & 15) >> 1); }
+
+// Word index (inside one unit's Vc) of the 16-token block tb = t/16 of channel c.
+__host__ __device__ inline uint32_t v_word_index(int tb, int c)
+{
+    return (uint32_t)(tb >> 2) * (4u * kD) + (uint32_t)c * 4u + (uint32_t)(tb & 3);
+}
+// Bit position of token t inside its V word.
+__host__ __device__ inline int v_bit(int t) { return 16 * (t & 1) + 2 * ((t & 15) >> 1); }
+
+// Decode launch geometry, derived from the shape alone so that the main kernel, the merge kernel and
+// minikv_workspace_bytes() agree.
+struct DecodeGeom {
+    int chunk;      // quantized tokens per workgroup
+    int nchunk;     // quantized-token chunks per unit (Tcap / chunk, rounded up)
+    int rep;        // query heads per KV head
+};
+DecodeGeom decode_geom(const minikv_shape &s);
+
+int validate_shape(const minikv_shape *s);
+
+// launchers (one per translation unit)
+int launch_quantize(const minikv_shape &s, const minikv_f16 *K, const minikv_f16 *V, int64_t L,
+                    const int32_t *idx, int64_t idx_stride, const int32_t *n_tok, int32_t max_tok,
+                    const minikv_cache &c, bool flush, hipStream_t st);
+int launch_append(const minikv_shape &s, const minikv_f16 *k_new, const minikv_f16 *v_new,
+                  const minikv_cache &c, hipStream_t st);
+int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
+                  minikv_f16 *out, float *ws, int variant, hipStream_t st);
+
+}  // namespace minikv

@@ -1,0 +1,245 @@
+// kv_quantize_pack / kv_flush_residual / kv_append_residual kernels (gfx950).
+//
+// Quantizer: Section 3.1.1 and Section 3.3 of the MiniKV paper -- asymmetric 2-bit codes, K grouped
+// along tokens per channel, V grouped along channels per token, fp16 scale and zero-point, 16 codes per
+// 32-bit word.  Residual buffer: Algorithm 1 lines 9-15.
+//
+// One workgroup of 256 threads takes a block of BT = max(64, G) consecutive retained tokens of one unit:
+// the fp16 rows are gathered (Algorithm 1 line 3: only retained rows are read) into LDS with 128-bit
+// loads, group statistics are taken from LDS, and each thread then builds whole 32-bit words so that
+// every store is a full word and consecutive threads write consecutive addresses.
+#include "common.h"
+
+#include <hip/hip_fp16.h>
+
+namespace minikv {
+
+struct QuantArgs {
+    const uint16_t *K, *V;       // [U][L][D] fp16
+    const int32_t *idx;          // [U][idx_stride] or null
+    const int32_t *n_tok;        // [U]  (flush: r_len)
+    uint32_t *Kc, *Vc;
+    uint16_t *Ks, *Kz, *Vs, *Vz;
+    int32_t *q_len, *r_len;
+    int64_t L, idx_stride;
+    int Tcap, Rcap, flush;
+};
+
+constexpr int kRow = kD + 8;     // LDS row pitch in halfs: 272 B keeps 16-B alignment, staggers banks
+
+__device__ inline float h2f(uint16_t h) { return __half2float(__ushort_as_half(h)); }
+
+// Tokens this unit appends, or 0 when the request is not a positive multiple of G that fits.
+template <int G>
+__device__ inline int tokens_to_append(const QuantArgs &a, int u, int &q0)
+{
+    int n = a.n_tok[u];
+    q0 = a.q_len[u];
+    if (a.flush) n = (n == a.Rcap) ? a.Rcap : 0;
+    if (n <= 0 || (n % G) || q0 < 0 || (q0 % G) || q0 + n > a.Tcap || n > a.L) return 0;
+    return n;
+}
+
+// scale (fp16 bits), zero (fp16 bits), 1/scale (binary32) of a group with extrema mn, mx.
+__device__ inline void group_params(float mn, float mx, uint16_t &sh, uint16_t &zh, float &inv, float &zf)
+{
+    __half z = __float2half_rn(mn);                   // exact: mn is an fp16 value
+    zh = __half_as_ushort(z);
+    if ((zh & 0x7fffu) == 0) zh = 0;                  // -0 is stored as +0
+    zf = h2f(zh);
+    float range = mx - mn;
+    float step = range / 3.0f;                        // IEEE binary32 division
+    __half s = __float2half_rn(step);
+    sh = __half_as_ushort(s);
+    float sf = __half2float(s);
+    inv = (sf == 0.0f) ? 0.0f : 1.0f / sf;
+}
+
+__device__ inline uint32_t quant_code(float x, float zf, float inv)
+{
+    float d = x - zf;
+    float u = d * inv;
+    float r = rintf(u);                               // round half to even
+    r = fminf(fmaxf(r, 0.0f), 3.0f);
+    return (uint32_t)(int)r;
+}
+
+template <int G>
+__device__ inline void load_rows(uint16_t *tile, const uint16_t *src, const QuantArgs &a, int u, int i0, int nt)
+{
+    const int tid = threadIdx.x;
+    for (int r = tid >> 4; r < nt; r += 16) {
+        long row = a.idx ? (long)a.idx[(size_t)u * a.idx_stride + i0 + r] : (long)(i0 + r);
+        row = row < 0 ? 0 : (row >= a.L ? a.L - 1 : row);
+        const uint4 *p = reinterpret_cast<const uint4 *>(src + ((size_t)u * a.L + row) * kD) + (tid & 15);
+        *reinterpret_cast<uint4 *>(tile + r * kRow + (tid & 15) * 8) = *p;
+    }
+}
+
+template <int G>
+__global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
+{
+    constexpr int BT = G > 64 ? G : 64;               // tokens per workgroup
+    constexpr int NCG = kD / G;                       // V channel groups per token
+    constexpr int NPAR = (BT / G) * kD > BT * NCG ? (BT / G) * kD : BT * NCG;
+
+    __shared__ __attribute__((aligned(16))) uint16_t tile[BT * kRow];
+    __shared__ float p_inv[NPAR];
+    __shared__ float p_zero[NPAR];
+
+    const int u = blockIdx.y;
+    const int tid = threadIdx.x;
+    int q0;
+    const int n = tokens_to_append<G>(a, u, q0);
+    const int i0 = blockIdx.x * BT;
+    if (i0 >= n) return;
+    const int nt = (n - i0 < BT) ? n - i0 : BT;        // multiple of G
+    const int t0 = q0 + i0;                            // first destination token, multiple of G
+
+    // ---------------- K: groups of G tokens per channel
+    load_rows<G>(tile, a.K, a, u, i0, nt);
+    __syncthreads();
+    for (int gi = tid; gi < (nt / G) * kD; gi += 256) {
+        const int g = gi / kD, c = gi % kD;
+        float mn = INFINITY, mx = -INFINITY;
+        for (int i = g * G; i < (g + 1) * G; i++) {
+            float x = h2f(tile[i * kRow + c]);
+            mn = fminf(mn, x);
+            mx = fmaxf(mx, x);
+        }
+        uint16_t sh, zh; float inv, zf;
+        group_params(mn, mx, sh, zh, inv, zf);
+        const size_t o = ((size_t)u * (a.Tcap / G) + (size_t)(t0 / G + g)) * kD + c;
+        a.Ks[o] = sh;
+        a.Kz[o] = zh;
+        p_inv[gi] = inv;
+        p_zero[gi] = zf;
+    }
+    __syncthreads();
+    {
+        uint32_t *Kc = a.Kc + (size_t)u * kc_words(a.Tcap);
+        const int npair = nt / 2;
+        for (int wi = tid; wi < nt * 8; wi += 256) {
+            const int wq = wi & 3;
+            const int pr = (wi >> 2) % npair;
+            const int ch = wi / (4 * npair);           // 0..3 = 2*(token parity) + (word half)
+            const int i = 2 * pr + (ch >> 1);
+            const int w = (ch & 1) * 4 + wq;
+            const int g = i / G;
+            uint32_t word = 0;
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                const int c = 16 * w + k;
+                float x = h2f(tile[i * kRow + c]);
+                word |= quant_code(x, p_zero[g * kD + c], p_inv[g * kD + c]) << k_bit(c);
+            }
+            Kc[k_word_index(t0 + i, w)] = word;
+        }
+    }
+    __syncthreads();
+
+    // ---------------- V: groups of G channels per token
+    load_rows<G>(tile, a.V, a, u, i0, nt);
+    __syncthreads();
+    for (int gi = tid; gi < nt * NCG; gi += 256) {
+        const int i = gi / NCG, cg = gi % NCG;
+        float mn = INFINITY, mx = -INFINITY;
+        for (int c = cg * G; c < (cg + 1) * G; c++) {
+            float x = h2f(tile[i * kRow + c]);
+            mn = fminf(mn, x);
+            mx = fmaxf(mx, x);
+        }
+        uint16_t sh, zh; float inv, zf;
+        group_params(mn, mx, sh, zh, inv, zf);
+        const size_t o = ((size_t)u * a.Tcap + (size_t)(t0 + i)) * NCG + cg;
+        a.Vs[o] = sh;
+        a.Vz[o] = zh;
+        p_inv[gi] = inv;
+        p_zero[gi] = zf;
+    }
+    __syncthreads();
+    {
+        uint32_t *Vc = a.Vc + (size_t)u * vc_words(a.Tcap);
+        const int nb = nt / 16;
+        for (int wi = tid; wi < nb * kD; wi += 256) {
+            const int bl = wi % nb, c = wi / nb;
+            const int cg = c / G;
+            uint32_t word = 0;
+#pragma unroll
+            for (int p = 0; p < 16; p++) {
+                const int i = 16 * bl + p;
+                float x = h2f(tile[i * kRow + c]);
+                word |= quant_code(x, p_zero[i * NCG + cg], p_inv[i * NCG + cg]) << v_bit(p);
+            }
+            Vc[v_word_index(t0 / 16 + bl, c)] = word;
+        }
+    }
+}
+
+// Runs after every workgroup of quantize_pack_kernel has finished (next kernel on the stream).
+template <int G>
+__global__ void update_lengths_kernel(QuantArgs a, int units)
+{
+    const int u = blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= units) return;
+    int q0;
+    const int n = tokens_to_append<G>(a, u, q0);
+    if (n == 0) return;
+    a.q_len[u] = q0 + n;
+    if (a.flush) a.r_len[u] = 0;
+}
+
+__global__ __launch_bounds__(64) void append_residual_kernel(const uint16_t *k_new, const uint16_t *v_new,
+                                                             uint16_t *Rk, uint16_t *Rv, int32_t *r_len,
+                                                             int Rcap)
+{
+    const int u = blockIdx.x, tid = threadIdx.x;
+    const int r = r_len[u];
+    __syncthreads();                                   // everyone has read r before it is bumped
+    if (r < 0 || r >= Rcap) return;
+    if (tid < 32) {
+        const uint16_t *src = (tid < 16 ? k_new : v_new) + (size_t)u * kD;
+        uint16_t *dst = (tid < 16 ? Rk : Rv) + ((size_t)u * Rcap + r) * kD;
+        reinterpret_cast<uint4 *>(dst)[tid & 15] = reinterpret_cast<const uint4 *>(src)[tid & 15];
+    }
+    if (tid == 0) r_len[u] = r + 1;
+}
+
+template <int G>
+static int launch_quantize_g(const QuantArgs &a, int units, int max_tok, hipStream_t st)
+{
+    constexpr int BT = G > 64 ? G : 64;
+    dim3 grid((max_tok + BT - 1) / BT, units);
+    hipLaunchKernelGGL(quantize_pack_kernel<G>, grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL(update_lengths_kernel<G>, dim3((units + 255) / 256), dim3(256), 0, st, a, units);
+    return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
+}
+
+int launch_quantize(const minikv_shape &s, const minikv_f16 *K, const minikv_f16 *V, int64_t L,
+                    const int32_t *idx, int64_t idx_stride, const int32_t *n_tok, int32_t max_tok,
+                    const minikv_cache &c, bool flush, hipStream_t st)
+{
+    QuantArgs a;
+    a.K = K; a.V = V; a.idx = idx; a.n_tok = n_tok;
+    a.Kc = c.Kc; a.Vc = c.Vc; a.Ks = c.Ks; a.Kz = c.Kz; a.Vs = c.Vs; a.Vz = c.Vz;
+    a.q_len = c.q_len; a.r_len = c.r_len;
+    a.L = L; a.idx_stride = idx_stride; a.Tcap = s.Tcap; a.Rcap = s.Rcap; a.flush = flush ? 1 : 0;
+    const int units = s.B * s.Hkv;
+    switch (s.G) {
+    case 16: return launch_quantize_g<16>(a, units, max_tok, st);
+    case 32: return launch_quantize_g<32>(a, units, max_tok, st);
+    case 64: return launch_quantize_g<64>(a, units, max_tok, st);
+    case 128: return launch_quantize_g<128>(a, units, max_tok, st);
+    }
+    return MINIKV_EUNSUPPORTED;
+}
+
+int launch_append(const minikv_shape &s, const minikv_f16 *k_new, const minikv_f16 *v_new,
+                  const minikv_cache &c, hipStream_t st)
+{
+    hipLaunchKernelGGL(append_residual_kernel, dim3(s.B * s.Hkv), dim3(64), 0, st, k_new, v_new, c.Rk,
+                       c.Rv, c.r_len, s.Rcap);
+    return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
+}
+
+}  // namespace minikv

@@ -1,0 +1,78 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, and its host-side
+argument validation returns the documented status codes before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_2411_18077_amd import api as _api
+    if not os.path.exists(_api.LIB_PATH):
+        from paper_2411_18077_amd import build
+        build.build(verbose=False)
+    return _api
+
+
+def test_exports_every_declared_symbol(api):
+    text = open(os.path.join(ROOT, "include", "minikv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(minikv_\w+|kv_\w+)\s*\(", text)
+    names = sorted(set(names))
+    assert {"kv_quantize_pack", "kv_append_residual", "kv_flush_residual", "minikv_decode_attn",
+            "minikv_workspace_bytes", "minikv_buffer_bytes", "minikv_abi_version"} <= set(names)
+    l = api.lib()
+    for n in names:
+        assert hasattr(l, n), n
+    assert l.minikv_abi_version() == 1
+
+
+def test_buffer_sizes_follow_the_documented_layout(api):
+    s = api.make_shape(2, 8, 4, 128, 32, 256, 64)
+    U = 8
+    want = [U * 2 * 1024 * 4, U * 8 * 128 * 2, U * 8 * 128 * 2, U * 4 * 4 * 128 * 4, U * 256 * 4 * 2, U * 256 * 4 * 2,
+            U * 4, U * 64 * 128 * 2, U * 64 * 128 * 2, U * 4]
+    assert [api.buffer_bytes(s, i) for i in range(10)] == want
+    # 64 + 8*D/G bytes per token
+    assert sum(want[:6]) == U * 256 * (64 + 8 * 128 // 32)
+    assert api.workspace_bytes(s) >= 2 * 8 * 2 * 132 * 4
+    assert api.buffer_bytes(api.make_shape(1, 1, 1, 64, 32, 128, 0), 0) == 0
+
+
+@pytest.mark.parametrize("bad,status", [
+    (dict(D=64), -2), (dict(G=8), -2), (dict(Tcap=100), -1), (dict(Rcap=40), -1), (dict(Hq=6, Hkv=4), -1),
+    (dict(Hq=32, Hkv=2), -2), (dict(B=0), -1),
+])
+def test_shape_rules_are_checked_on_the_host(api, bad, status):
+    kw = dict(B=1, Hq=4, Hkv=4, D=128, G=32, Tcap=256, Rcap=32)
+    kw.update(bad)
+    s = api.make_shape(**kw)
+    cache = api.MinikvCache(*([0x1000] * 10))
+    rc = api.lib().minikv_decode_attn(C.byref(s), C.c_void_p(0x1000), C.byref(cache), 1.0, C.c_void_p(0x1000),
+                                      C.c_void_p(0x1000), 1 << 30, None)
+    assert rc == status
+    assert api.lib().minikv_strerror(rc)
+
+
+def test_pointer_and_workspace_checks(api):
+    s = api.make_shape(1, 4, 4, 128, 32, 256, 32)
+    l = api.lib()
+    good = api.MinikvCache(*([0x1000] * 10))
+    P = C.c_void_p
+    assert l.minikv_decode_attn(C.byref(s), P(0x1000), C.byref(good), 1.0, P(0x1000), P(0x1000), 16, None) == -3
+    assert l.minikv_decode_attn(C.byref(s), None, C.byref(good), 1.0, P(0x1000), P(0x1000), 1 << 30, None) == -1
+    assert l.minikv_decode_attn(C.byref(s), P(0x1008), C.byref(good), 1.0, P(0x1000), P(0x1000), 1 << 30, None) == -1
+    assert l.minikv_decode_attn(C.byref(s), P(0x1000), C.byref(good), float("nan"), P(0x1000), P(0x1000), 1 << 30, None) == -1
+    bad = api.MinikvCache(*([0x1000] * 3 + [0] + [0x1000] * 6))
+    assert l.minikv_decode_attn(C.byref(s), P(0x1000), C.byref(bad), 1.0, P(0x1000), P(0x1000), 1 << 30, None) == -1
+    assert l.kv_append_residual(C.byref(s), None, P(0x1000), C.byref(good), None) == -1
+    assert l.kv_quantize_pack(C.byref(s), P(0x1000), P(0x1000), 64, None, 0, P(0x1000), 48, C.byref(good), None) == -1
+    assert l.kv_quantize_pack(C.byref(s), P(0x1000), P(0x1000), 64, None, 0, P(0x1000), 512, C.byref(good), None) == -1
+    assert l.kv_quantize_pack(C.byref(s), P(0x1000), P(0x1000), 64, P(0x1000), 16, P(0x1000), 32, C.byref(good), None) == -1
+    assert l.kv_quantize_pack(C.byref(s), P(0x1000), P(0x1000), 64, None, 0, P(0x1000), 0, C.byref(good), None) == 0
+    assert l.minikv_set_variant(99) == -1 and l.minikv_set_variant(0) == 0
+    assert b"workspace" in l.minikv_strerror(-3)

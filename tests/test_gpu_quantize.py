@@ -1,0 +1,120 @@
+"""GPU parity for kv_quantize_pack / kv_append_residual / kv_flush_residual: codes, packed words, scale
+and zero-point must equal the oracle's bit for bit (Section 3.1.1 / 3.3; Algorithm 1 lines 3-5, 9-15)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2411_18077_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    import gpu_common
+    assert torch.cuda.is_available()
+    return gpu_common
+
+
+def small(G, **kw):
+    base = dict(name="t", B=2, Hq=4, Hkv=2, L=640, keep=0.5, G=G, Rcap=max(G, 32), seed=40 + G,
+                n_outlier=3, outlier_scale=8.0)
+    base.update(kw)
+    return W.Workload(**base)
+
+
+@pytest.mark.parametrize("G", [16, 32, 64, 128])
+def test_prefill_quantize_bit_exact(g, G):
+    w = small(G)
+    inp = W.make_inputs(w, "cuda")
+    s, rs = g.shapes_for(w, inp.Tcap)
+    gc = g.gpu_build_cache(inp, s)
+    rc = g.ref_build_cache(inp, rs)
+    assert int(gc.q_len[0]) == int(inp.n_tok[0]) > 0
+    g.assert_cache_bit_exact(gc, rc)
+
+
+def test_ragged_lengths_student_t_and_no_gather(g):
+    w = small(64, keep=None, keep_range=(0.05, 1.0), dist="student_t4", L=1024, B=3, Hkv=2, Hq=2, n_outlier=0)
+    inp = W.make_inputs(w, "cuda")
+    s, rs = g.shapes_for(w, inp.Tcap)
+    g.assert_cache_bit_exact(g.gpu_build_cache(inp, s), g.ref_build_cache(inp, rs))
+    # idx == NULL takes rows 0..n-1
+    from paper_2411_18077_amd import api
+    from oracle import ref
+    cache = api.Cache(s)
+    api.kv_quantize_pack(s, inp.K, inp.V, w.L, None, 0, inp.n_tok, int(inp.n_tok.max()), cache)
+    torch.cuda.synchronize()
+    c = ref.RefCache(rs)
+    assert ref.quantize_pack(c, g.to_np(inp.K), g.to_np(inp.V), g.to_np(inp.n_tok), None) == 0
+    g.assert_cache_bit_exact(cache, c)
+
+
+def test_lattice_and_ties_bit_exact(g):
+    """Exact half-way cases (round half to even) and degenerate groups reach the GPU rounding path."""
+    w = small(16, L=256, keep=1.0, n_outlier=0)
+    inp = W.make_inputs(w, "cuda")
+    gen = torch.Generator(device="cuda"); gen.manual_seed(5)
+    lev = torch.randint(0, 13, inp.K.shape, generator=gen, device="cuda").to(torch.float16) * 0.25   # 0..3 in steps of 1/4
+    lev[:, 0::16] = 0; lev[:, 1::16] = 3
+    inp.K.copy_(lev)
+    v = torch.randint(0, 7, inp.V.shape, generator=gen, device="cuda").to(torch.float16) * 0.5
+    v[:, :, 0::16] = 0; v[:, :, 1::16] = 3
+    v[:, 5] = 1.25                                      # degenerate groups: max == min
+    v[:, 6] = -0.0
+    inp.V.copy_(v)
+    s, rs = g.shapes_for(w, inp.Tcap)
+    g.assert_cache_bit_exact(g.gpu_build_cache(inp, s), g.ref_build_cache(inp, rs))
+
+
+def test_refused_units_are_left_unchanged(g):
+    from paper_2411_18077_amd import api
+    w = small(32, L=256, keep=1.0)
+    inp = W.make_inputs(w, "cuda")
+    s, _ = g.shapes_for(w, inp.Tcap)
+    cache = api.Cache(s)
+    n = inp.n_tok.clone(); n[1] = 40                     # not a multiple of G
+    cache.q_len[2] = inp.Tcap - 32                       # would overflow the capacity
+    api.kv_quantize_pack(s, inp.K, inp.V, w.L, None, 0, n, 256, cache)
+    torch.cuda.synchronize()
+    q = cache.q_len.cpu().tolist()
+    assert q[0] == 256 and q[1] == 0 and q[2] == inp.Tcap - 32 and q[3] == 256
+
+
+def test_decode_loop_append_and_flush_bit_exact(g):
+    """Algorithm 1 lines 9-15 over 2*n_r + 5 steps on both sides; every buffer equal after every flush."""
+    from paper_2411_18077_amd import api
+    from oracle import ref
+    w = small(32, L=256, keep=0.5, Rcap=32)
+    inp = W.make_inputs(w, "cuda")
+    Tcap = 384
+    s, rs = g.shapes_for(w, Tcap)
+    gc = g.gpu_build_cache(inp, s)
+    rc = g.ref_build_cache(inp, rs)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(9)
+    steps = 2 * w.Rcap + 5
+    for i in range(steps):
+        k = torch.randn(w.units, w.D, generator=gen, device="cuda").to(torch.float16)
+        v = torch.randn(w.units, w.D, generator=gen, device="cuda").to(torch.float16)
+        api.kv_append_residual(s, k, v, gc)
+        api.kv_flush_residual(s, gc)
+        assert ref.append_residual(rc, g.to_np(k), g.to_np(v)) == 0
+        assert ref.flush_residual(rc) == 0
+        if (i + 1) % w.Rcap in (0, 1) or i == steps - 1:
+            torch.cuda.synchronize()
+            assert gc.r_len.cpu().tolist() == rc.r_len.tolist()
+            assert gc.q_len.cpu().tolist() == rc.q_len.tolist()
+            g.assert_cache_bit_exact(gc, rc, what=("Kc", "Ks", "Kz", "Vc", "Vs", "Vz"))
+            r = int(rc.r_len[0])
+            assert np.array_equal(g.to_np(gc.Rk).reshape(w.units, w.Rcap, w.D)[:, :r], rc.Rk[:, :r])
+    # a full residual refuses a further token
+    for i in range(w.Rcap):
+        api.kv_append_residual(s, k, v, gc)
+    torch.cuda.synchronize()
+    assert gc.r_len.cpu().tolist() == [w.Rcap] * w.units
+    before = gc.Rk.clone()
+    api.kv_append_residual(s, k + 1, v, gc)
+    torch.cuda.synchronize()
+    assert gc.r_len.cpu().tolist() == [w.Rcap] * w.units and torch.equal(before, gc.Rk)
