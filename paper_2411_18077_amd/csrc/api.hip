@@ -16,7 +16,7 @@ int validate_shape(const minikv_shape *s)
     if (s->Hq / s->Hkv > kMaxRep) return MINIKV_EUNSUPPORTED;
     if (s->Tcap <= 0 || s->Tcap % kKTile) return MINIKV_EINVAL;
     if (s->Rcap < 0 || s->Rcap % s->G) return MINIKV_EINVAL;
-    if ((int64_t)s->B * s->Hkv > (1 << 22)) return MINIKV_EINVAL;
+    if ((int64_t)s->B * s->Hkv > 65535) return MINIKV_EINVAL;      // units index a grid dimension
     return MINIKV_OK;
 }
 
