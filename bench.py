@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the MiniKV decode step on one MI355X.
+
+One "step" = kv_append_residual (the new token's K/V row) + minikv_decode_attn over a 2-bit, evicted
+cache, i.e. the per-token hot path of Algorithm 1's Decoding procedure.  Every step runs on its OWN
+seeded cache copy (different data, different addresses), so nothing is served from L2 or the Infinity
+Cache and no state has to be reset inside the timed region; all inputs are resident in HBM before the
+clock starts.  The prefill-side kv_quantize_pack and the flush are timed separately and reported in
+extra fields of the same JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4] [--variant V]
+
+Prints ONE JSON line (see the keys below).  `value` is effective HBM GB/s = algorithmic bytes per step
+/ time per step; `roofline` is the decode kernel against the 8 TB/s HBM peak; `cpu_baseline` is the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg4")
+    ap.add_argument("--variant", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--max-copies", type=int, default=0, help="cap on distinct cache copies (0: steps+warmup)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures ONE GPU (the decode path shards over (batch, KV-head) units with "
+              "no communication); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2411_18077_amd import api
+    from paper_2411_18077_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    api.lib()                                             # fails loudly when libminikv.so is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = W.by_name(args.workload)
+    sm = 1.0 / math.sqrt(w.D)
+    api.minikv_set_variant(args.variant)
+
+    # ------------------------------------------------------------------ build the cache copies
+    ncopy = args.steps + args.warmup
+    if args.max_copies:
+        ncopy = min(ncopy, args.max_copies)
+    free_b, _ = torch.cuda.mem_get_info()
+    copies = []
+    shape = None
+    sample_src = None
+    t_build = time.time()
+    quant_times = []
+    for i in range(ncopy):
+        inp = W.make_inputs(w, dev, seed_offset=i)
+        if shape is None:
+            shape = api.make_shape(w.B, w.Hq, w.Hkv, w.D, w.G, inp.Tcap, w.Rcap)
+        cache = api.Cache(shape, device=dev)
+        n_max = int(inp.n_tok.max())
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        api.kv_quantize_pack(shape, inp.K, inp.V, w.L, inp.idx, inp.idx.shape[1], inp.n_tok, n_max, cache)
+        e1.record()
+        # residual holds Rcap-1 tokens; the timed step appends the last one
+        r0 = w.Rcap - 1
+        cache.Rk.view(w.units, w.Rcap, w.D)[:, :r0].copy_(inp.Rk[:, :r0])
+        cache.Rv.view(w.units, w.Rcap, w.D)[:, :r0].copy_(inp.Rv[:, :r0])
+        cache.r_len.fill_(r0)
+        k_new = inp.Rk[:, r0].contiguous()
+        v_new = inp.Rv[:, r0].contiguous()
+        out = torch.zeros(w.B, w.Hq, w.D, dtype=torch.float16, device=dev)
+        torch.cuda.synchronize()
+        quant_times.append(e0.elapsed_time(e1))
+        copies.append(dict(cache=cache, q=inp.q, k_new=k_new, v_new=v_new, out=out, n_tok=inp.n_tok))
+        if i == 0:
+            sample_src = inp                               # kept for the parity / cpu-baseline sample
+            gathered_bytes = int(inp.n_tok.sum()) * w.D * 2 * 2 + int(inp.n_tok.sum()) * (64 + 8 * w.D // w.G)
+        else:
+            del inp
+        if i == 1 and (ncopy - 2) * (cache.nbytes() + 64 * 2**20) > torch.cuda.mem_get_info()[0] * 0.8:
+            ncopy = max(2, int(torch.cuda.mem_get_info()[0] * 0.8 / (cache.nbytes() + 64 * 2**20)))
+    ncopy = len(copies)
+    t_build = time.time() - t_build
+
+    q_len = copies[0]["n_tok"].cpu().tolist()
+    alg_bytes = W.algorithmic_bytes(w, q_len, [w.Rcap] * w.units)
+    append_bytes = 2 * w.units * w.D * 2 * 2               # read + write of the new K and V rows
+
+    def step(i):
+        c = copies[i % ncopy]
+        api.kv_append_residual(shape, c["k_new"], c["v_new"], c["cache"])
+        api.minikv_decode_attn(shape, c["q"], c["cache"], sm, c["out"])
+
+    # ------------------------------------------------------------------ timed region
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = alg_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ------------------------------------------------------------------ per-launch timing of the attention call (events)
+    evs = []
+    for i in range(args.steps):
+        c = copies[(args.warmup + i) % ncopy]
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        api.minikv_decode_attn(shape, c["q"], c["cache"], sm, c["out"])
+        b.record()
+        evs.append((a, b))
+    torch.cuda.synchronize()
+    durs = sorted(a.elapsed_time(b) for a, b in evs)
+    attn_ms_avg = sum(durs) / len(durs)
+    attn_ms_med = durs[len(durs) // 2]
+    achieved = alg_bytes / (attn_ms_avg * 1e-3) / 1e9
+
+    result = {
+        "metric": "decode_attn_effective_hbm_bandwidth_2bit_kv",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "us_per_step": round(ms_per_step * 1e3, 2),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u2 codes, fp16 operands, fp32 accumulate",
+        "data": "synthetic",
+        "config": {
+            "workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "context": w.L,
+            "retained_per_unit": int(max(q_len)) if w.keep is not None else "ragged %d..%d" % (min(q_len), max(q_len)),
+            "G": w.G, "residual": w.Rcap, "Tcap": int(shape.Tcap), "cache_copies": ncopy,
+            "algorithmic_bytes_per_step": alg_bytes, "variant": args.variant,
+            "step": "kv_append_residual + minikv_decode_attn",
+        },
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 1),
+        "roofline": {
+            "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+            "kernel": "minikv_decode_attn (tile kernel + split-K merge)",
+            "avg_launch_us": round(attn_ms_avg * 1e3, 2), "median_launch_us": round(attn_ms_med * 1e3, 2),
+        },
+    }
+
+    # ------------------------------------------------------------------ parity + CPU baseline on a bounded sample
+    if not args.no_cpu_baseline:
+        from oracle import ref
+        import numpy as np
+        nsamp = min(w.units, 16)
+        rng = np.random.default_rng(w.seed)
+        units = sorted(rng.choice(w.units, nsamp, replace=False).tolist())
+        if w.keep is None:                                 # ragged: make sure the extremes are in
+            units = sorted(set(units[:-2] + [int(np.argmin(q_len)), int(np.argmax(q_len))]))
+            nsamp = len(units)
+        rep = w.Hq // w.Hkv
+        inp = sample_src
+        sel = torch.as_tensor(units, device=dev)
+        rs = ref.RefShape(nsamp, rep, 1, w.D, w.G, int(shape.Tcap), w.Rcap)
+        rc = ref.RefCache(rs)
+        t_q0 = time.perf_counter()
+        assert ref.quantize_pack(rc, inp.K[sel].cpu().numpy(), inp.V[sel].cpu().numpy(),
+                                 inp.n_tok[sel].cpu().numpy(), inp.idx[sel].cpu().numpy()) == 0
+        t_q1 = time.perf_counter()
+        rc.Rk[:] = inp.Rk[sel].cpu().numpy(); rc.Rv[:] = inp.Rv[sel].cpu().numpy(); rc.r_len[:] = w.Rcap
+        qs = inp.q.view(w.B, w.Hkv, rep, w.D).reshape(w.units, rep, w.D)[sel].cpu().numpy()
+        times = []
+        for _ in range(3):
+            a = time.perf_counter()
+            want, _, _ = ref.decode_attn(rc, qs, sm)
+            times.append(time.perf_counter() - a)
+        cpu_s = sorted(times)[1]
+        samp_bytes = W.algorithmic_bytes(w, [q_len[u] for u in units], [w.Rcap] * nsamp)
+        got = copies[0]["out"].view(w.B, w.Hkv, rep, w.D).reshape(w.units, rep, w.D)[sel].float().cpu().numpy()
+        # copies[0] was last run in the event loop or the timed loop; its output is the step's result
+        err = float(np.max(np.abs(got - want.astype(np.float32))))
+        result["parity"] = {"max_abs_err_vs_oracle": err, "tolerance": 2e-3, "sample_units": nsamp,
+                            "ok": bool(err <= 2e-3)}
+        result["cpu_baseline"] = {
+            "value": round(samp_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())),
+            "kind": "oracle",
+            "sample": "%d of %d (batch, KV-head) units of %s, all query heads, median of 3 runs (%.2f s each)"
+                      % (nsamp, w.units, w.name, cpu_s),
+            "quantize_pack_s": round(t_q1 - t_q0, 3),
+        }
+
+    if not args.no_extras:
+        qt = sorted(quant_times[1:] or quant_times)
+        q_ms = qt[len(qt) // 2]
+        result["quantize_pack"] = {
+            "what": "kv_quantize_pack of the retained rows (gather + quantize + pack), median over the cache copies",
+            "ms": round(q_ms, 4), "bytes": gathered_bytes, "GB/s": round(gathered_bytes / (q_ms * 1e-3) / 1e9, 1),
+        }
+        # flush: every unit quantizes its full residual (n_r tokens) into the packed cache
+        c = copies[0]
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        api.kv_flush_residual(shape, c["cache"])
+        b.record()
+        torch.cuda.synchronize()
+        result["flush_residual"] = {"ms": round(a.elapsed_time(b), 4), "tokens_per_unit": w.Rcap,
+                                    "amortised_us_per_step": round(a.elapsed_time(b) * 1e3 / w.Rcap, 3)}
+        result["build_s"] = round(t_build, 1)
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

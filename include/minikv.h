@@ -35,7 +35,9 @@
  *       the token's word w = c/16 at bit 16*(c%2) + 2*((c%16)/2) (even channels in the low half-word,
  *       odd channels in the high one).  Word index = (t/128)*1024 + ((2*(t%2) + w/4)*64 + (t%128)/2)*4
  *       + w%4.
- *   Ks, Kz  fp16 [Tcap/G][D]          scale / zero of token group t/G, channel c.
+ *   Ks, Kz  fp16 [Tcap/G][D]          scale / zero of token group t/G.  Inside a row channel c sits at
+ *       position ((q % NB)*(32/NB) + q/NB)*4 + c%4 with q = c/4 and NB = G/8: the 32 channel quads
+ *       are dealt round-robin into NB bins, bin after bin.
  *   Vc  uint32 [Tcap/64][D][4]        one word = 16 consecutive tokens of ONE channel: token t is in
  *       block (t%64)/16 at bit 16*(t%2) + 2*((t%16)/2).  Word index = (t/64)*4*D + c*4 + (t%64)/16.
  *   Vs, Vz  fp16 [Tcap][D/G]          scale / zero of token t, channel group c/G.

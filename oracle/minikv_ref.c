@@ -94,6 +94,14 @@ static size_t v_slot(int D, int t, int c, int *bit)
     return (size_t)tile * 4 * (size_t)D + (size_t)c * 4 + (size_t)(tau / 16);
 }
 
+/* position of channel c inside a K scale / zero row: the 32 channel quads are dealt round-robin into
+ * NB = G/8 bins, bin after bin */
+int ref_k_meta_pos(int G, int c)
+{
+    int nb = G / 8, q = c / 4;
+    return ((q % nb) * (32 / nb) + q / nb) * 4 + c % 4;
+}
+
 static size_t kc_words(const ref_shape *s) { return (size_t)s->Tcap / 128 * 1024; }
 static size_t vc_words(const ref_shape *s) { return (size_t)s->Tcap / 64 * 4 * (size_t)s->D; }
 
@@ -157,7 +165,7 @@ static void quantize_unit(const ref_shape *s, ref_cache *c, size_t u, const uint
             }
             uint16_t sh, zh; float inv;
             group_params(mn, mx, &sh, &zh, &inv);
-            size_t gidx = (size_t)((t0 + g0) / G) * D + ch;
+            size_t gidx = (size_t)((t0 + g0) / G) * D + ref_k_meta_pos(G, ch);
             Ks[gidx] = sh;
             Kz[gidx] = zh;
             float zf = ref_f16_to_f32(zh);
@@ -300,7 +308,7 @@ int ref_dequant(const ref_shape *s, const ref_cache *c, int unit, double *Khat, 
     const uint16_t *Vz = c->Vz + (size_t)unit * s->Tcap * (D / G);
     for (int t = 0; t < T; t++)
         for (int ch = 0; ch < D; ch++) {
-            size_t kg = (size_t)(t / G) * D + ch;
+            size_t kg = (size_t)(t / G) * D + ref_k_meta_pos(G, ch);
             size_t vg = (size_t)t * (D / G) + ch / G;
             if (Khat) Khat[(size_t)t * D + ch] =
                 (double)kc[(size_t)t * D + ch] * (double)ref_f16_to_f32(Ks[kg]) + (double)ref_f16_to_f32(Kz[kg]);
@@ -356,7 +364,7 @@ int minikv_decode_attn_ref(const ref_shape *s, const uint16_t *q, const ref_cach
                 int bit;
                 size_t w = k_slot(t, ch, &bit);
                 double code = (double)((Kc[w] >> bit) & 3u);
-                size_t g = (size_t)(t / G) * D + ch;
+                size_t g = (size_t)(t / G) * D + ref_k_meta_pos(G, ch);
                 double khat = code * (double)ref_f16_to_f32(Ks[g]) + (double)ref_f16_to_f32(Kz[g]);
                 acc += qd[ch] * khat;
             }

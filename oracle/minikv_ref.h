@@ -19,6 +19,8 @@
  *   V: one word = 16 consecutive tokens of ONE channel.  Token t, channel c: block = (t%64)/16,
  *      bit 16*(t%2) + 2*((t%16)/2); tiles of 64 tokens:  word index = (t/64)*4*D + c*4 + block.
  *   Scale / zero-point: fp16, K [Tcap/G][D] per unit (token-group major), V [Tcap][D/G] per unit.
+ *      Inside a K row channel c sits at ((q % NB)*(32/NB) + q/NB)*4 + c%4 with q = c/4, NB = G/8
+ *      (the 32 channel quads dealt round-robin into NB bins).
  *
  * Pins (tests/ with -m "not gpu"): round-trip half-step bound, code 0/3 presence, lossless lattice,
  * fp64 arg-min brute force with explicit ties, hand-derived packed words, Appendix I size arithmetic,
@@ -84,6 +86,9 @@ int minikv_decode_attn_ref(const ref_shape *s, const uint16_t *q, const ref_cach
 /* Layout-free views for tests: codes[unit][t][ch] (0..3) and the dequantized values code*s+z. */
 int ref_unpack_codes(const ref_shape *s, const ref_cache *c, int unit, uint8_t *Kcodes, uint8_t *Vcodes);
 int ref_dequant(const ref_shape *s, const ref_cache *c, int unit, double *Khat, double *Vhat);
+
+/* Position of channel c inside a K scale / zero row (see the storage order above). */
+int ref_k_meta_pos(int G, int c);
 
 /* Appendix I: bytes of one packed group of G codes with its fp16 scale and zero-point. */
 size_t ref_group_bytes(int G);

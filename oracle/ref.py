@@ -36,7 +36,8 @@ def lib():
         _lib.ref_group_bytes.restype = C.c_size_t
         _lib.ref_group_bytes.argtypes = [C.c_int]
         for name in ("ref_check_shape", "kv_quantize_pack_ref", "kv_append_residual_ref",
-                     "kv_flush_residual_ref", "minikv_decode_attn_ref", "ref_unpack_codes", "ref_dequant"):
+                     "kv_flush_residual_ref", "minikv_decode_attn_ref", "ref_unpack_codes", "ref_dequant",
+                     "ref_k_meta_pos"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -148,6 +149,12 @@ def dequant(cache: RefCache, unit):
     rc = lib().ref_dequant(C.byref(s.c()), C.byref(cc), C.c_int(unit), _p(kh), _p(vh))
     assert rc == 0
     return kh[:T], vh[:T]
+
+
+def k_meta_perm(G, D=128):
+    """perm[c] = position of channel c inside a stored K scale / zero row; natural = stored[..., perm]."""
+    l = lib()
+    return np.array([l.ref_k_meta_pos(C.c_int(G), C.c_int(c)) for c in range(D)], dtype=np.int64)
 
 
 def group_bytes(G):

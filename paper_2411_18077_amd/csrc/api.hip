@@ -2,6 +2,7 @@
 #include "common.h"
 
 #include <atomic>
+#include <cstdlib>
 
 namespace minikv {
 
@@ -27,6 +28,7 @@ DecodeGeom decode_geom(const minikv_shape &s)
     const long units = (long)s.B * s.Hkv;
     int chunk = kMinChunk;
     while (chunk < 4096 && units * ((s.Tcap + 2 * chunk - 1) / (2 * chunk)) >= 2048) chunk *= 2;
+    if (const char *e = getenv("MINIKV_CHUNK")) { int v = atoi(e); if (v >= 512 && v % 512 == 0) chunk = v; }
     DecodeGeom g;
     g.chunk = chunk;
     g.nchunk = (s.Tcap + chunk - 1) / chunk;
@@ -143,7 +145,7 @@ int minikv_decode_attn(const minikv_shape *s, const minikv_f16 *q, const minikv_
 
 int minikv_set_variant(int variant)
 {
-    if (variant < 0 || variant > 3) return MINIKV_EINVAL;
+    if (variant < 0 || variant > 4 || variant == 2) return MINIKV_EINVAL;
     g_variant.store(variant);
     return MINIKV_OK;
 }
@@ -153,8 +155,8 @@ const char *minikv_strvariant(int variant)
     switch (variant) {
     case 0: return "default";
     case 1: return "scalar: plain per-token loops, fp32 FMA (cross-check kernel)";
-    case 2: return "wave-tiled, packed-fp16 dot products on the vector ALU";
     case 3: return "wave-tiled, 4x4x4 fp16 matrix-core blocks for the head x channel products";
+    case 4: return "as 3 but the q*Ks table keeps only its rounded fp16 value (no exact hi+lo pair)";
     default: return "unknown";
     }
 }

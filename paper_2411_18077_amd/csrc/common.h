@@ -28,6 +28,14 @@ __host__ __device__ inline uint32_t k_word_index(int t, int w)
 // Bit position of channel c inside its K word.
 __host__ __device__ inline int k_bit(int c) { return 16 * (c & 1) + 2 * ((c & 15) >> 1); }
 
+// Position of channel c inside a K scale / zero row: the 32 channel quads are dealt round-robin into
+// NB = G/8 bins so that every lane of the decode kernel finds its quads contiguous.
+__host__ __device__ inline int k_meta_pos(int G, int c)
+{
+    const int nb = G >> 3, q = c >> 2;
+    return ((q % nb) * (32 / nb) + q / nb) * 4 + (c & 3);
+}
+
 // Word index (inside one unit's Vc) of the 16-token block tb = t/16 of channel c.
 __host__ __device__ inline uint32_t v_word_index(int tb, int c)
 {

@@ -26,7 +26,7 @@ __device__ inline float *partial_ptr(const DecArgs &a, int bq, int ch)
 __device__ inline int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 int launch_decode_scalar(const DecArgs &a, int G, int units, hipStream_t st);
-int launch_decode_tiled(const DecArgs &a, int G, int units, bool mfma, hipStream_t st);
+int launch_decode_tiled(const DecArgs &a, int G, int units, int variant, hipStream_t st);
 int launch_merge(const DecArgs &a, int nq, hipStream_t st);
 
 }  // namespace minikv

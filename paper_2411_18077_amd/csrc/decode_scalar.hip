@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void decode_scalar_kernel(DecArgs a)
                     for (int k = 0; k < 16; k++) {
                         const int cc = 16 * w + k;
                         const float code = (float)((word >> k_bit(cc)) & 3u);
-                        const size_t g = (size_t)(t / G) * kD + cc;
+                        const size_t g = (size_t)(t / G) * kD + k_meta_pos(G, cc);
                         const float khat = code * hf(Ks[g]) + hf(Kz[g]);
                         for (int h = 0; h < rep; h++) acc[h] += q2[h][cc] * khat;
                     }
@@ -201,9 +201,9 @@ int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache
     a.chunk = g.chunk; a.nchunk = g.nchunk;
     const int units = s.B * s.Hkv;
     int rc;
-    if (variant == 0) variant = 1;                     // default variant
+    if (variant == 0) variant = 3;                     // default variant
     if (variant == 1) rc = launch_decode_scalar(a, s.G, units, st);
-    else rc = launch_decode_tiled(a, s.G, units, variant == 3, st);
+    else rc = launch_decode_tiled(a, s.G, units, variant, st);
     if (rc) return rc;
     return launch_merge(a, s.B * s.Hq, st);
 }

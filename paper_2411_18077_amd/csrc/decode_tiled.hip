@@ -41,7 +41,6 @@ typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
 constexpr int kNH = 4;                 // query-head slots per workgroup (rows of the 4x4x4 blocks)
 constexpr int kPass = 128;             // tokens per wave pass
-constexpr int kQsG = 32 * 16 + 16;     // halfs per K-group table: 32 k-steps x (4 heads x 4 ch) + pad
 constexpr int kPsH = kPass + 4;        // halfs per (channel group, head) row of ps, padded
 constexpr int kPsG = kNH * kPsH;       // halfs per channel group of ps (528: shifts 8 banks)
 
@@ -60,16 +59,107 @@ __device__ inline h2 field(uint32_t w, uint32_t w6, int j)
     return as_h2((fld_shifted(j) ? w6 : w) & (0x00030003u << fld_shift(j)));
 }
 
+// ---- cross-lane reductions on the DPP data path (no LDS traffic)
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ inline float dpp_mov(float old, float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old), __builtin_bit_cast(int, v),
+                                                                  CTRL, ROW_MASK, 0xF, false));
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140,
+              kDppBcast15 = 0x142, kDppBcast31 = 0x143;
+
+// maximum over the 64 lanes, returned wave-uniform
 __device__ inline float wave_max64(float v)
 {
-    for (int o = 32; o; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    v = fmaxf(v, dpp_mov<kDppXor1>(v, v));
+    v = fmaxf(v, dpp_mov<kDppXor2>(v, v));
+    v = fmaxf(v, dpp_mov<kDppHalfMirror>(v, v));
+    v = fmaxf(v, dpp_mov<kDppMirror>(v, v));               // every row of 16 lanes now holds its maximum
+    v = fmaxf(v, dpp_mov<kDppBcast15, 0xA>(v, v));         // rows 1 and 3 take in rows 0 and 2
+    v = fmaxf(v, dpp_mov<kDppBcast31, 0xC>(v, v));         // rows 2 and 3 take in lane 31
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+// sum over aligned groups of N lanes (N = 4, 8 or 16), result in every lane of the group
+template <int N>
+__device__ inline float row_sum(float v)
+{
+    v += dpp_mov<kDppXor1>(v, v);
+    v += dpp_mov<kDppXor2>(v, v);
+    if constexpr (N >= 8) v += dpp_mov<kDppHalfMirror>(v, v);
+    if constexpr (N >= 16) v += dpp_mov<kDppMirror>(v, v);
     return v;
 }
+// sum over the 64 lanes, returned wave-uniform
 __device__ inline float wave_sum64(float v)
 {
-    for (int o = 32; o; o >>= 1) v += __shfl_xor(v, o);
+    v = row_sum<16>(v);
+    v += dpp_mov<kDppBcast15, 0xA>(0.f, v);
+    v += dpp_mov<kDppBcast31, 0xC>(0.f, v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+// sum over aligned groups of N lanes for N up to 64
+template <int N>
+__device__ inline float group_sum(float v)
+{
+    if constexpr (N <= 16) return row_sum<N>(v);
+    v = row_sum<16>(v);
+    v += __shfl_xor(v, 16);
+    if constexpr (N == 64) v += __shfl_xor(v, 32);
     return v;
 }
+// Four independent reductions at once, hand-scheduled: step k of all four values is issued back to back,
+// so the two wait states a DPP read needs after a VALU write are always covered by the other three.
+#define MINIKV_DPP4(op, ctrl)                                                     \
+    "v_" op "_f32_dpp %0, %0, %0 " ctrl " bank_mask:0xf\n"                        \
+    "v_" op "_f32_dpp %1, %1, %1 " ctrl " bank_mask:0xf\n"                        \
+    "v_" op "_f32_dpp %2, %2, %2 " ctrl " bank_mask:0xf\n"                        \
+    "v_" op "_f32_dpp %3, %3, %3 " ctrl " bank_mask:0xf\n"
+#define MINIKV_ROW16(op)                                                          \
+    MINIKV_DPP4(op, "quad_perm:[1,0,3,2] row_mask:0xf")                           \
+    MINIKV_DPP4(op, "quad_perm:[2,3,0,1] row_mask:0xf")                           \
+    MINIKV_DPP4(op, "row_half_mirror row_mask:0xf")                               \
+    MINIKV_DPP4(op, "row_mirror row_mask:0xf")
+#define MINIKV_WAVE64(op)                                                         \
+    MINIKV_ROW16(op)                                                              \
+    MINIKV_DPP4(op, "row_bcast:15 row_mask:0xa")                                  \
+    MINIKV_DPP4(op, "row_bcast:31 row_mask:0xc")
+
+__device__ inline float lane63(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+// v[i] <- maximum of v[i] over the wave (wave-uniform)
+__device__ inline void wave_max64x4(float v[4])
+{
+    asm volatile("s_nop 1\n" MINIKV_WAVE64("max") : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
+    for (int i = 0; i < 4; i++) v[i] = lane63(v[i]);
+}
+// v[i] <- sum of v[i] over the wave (wave-uniform)
+__device__ inline void wave_sum64x4(float v[4])
+{
+    asm volatile("s_nop 1\n" MINIKV_WAVE64("add") : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
+    for (int i = 0; i < 4; i++) v[i] = lane63(v[i]);
+}
+// v[i] <- sum over aligned groups of N lanes, in every lane of the group
+template <int N>
+__device__ inline void group_sum_x4(float v[4])
+{
+    if constexpr (N == 8) {
+        asm volatile("s_nop 1\n" MINIKV_DPP4("add", "quad_perm:[1,0,3,2] row_mask:0xf")
+                     MINIKV_DPP4("add", "quad_perm:[2,3,0,1] row_mask:0xf")
+                     MINIKV_DPP4("add", "row_half_mirror row_mask:0xf")
+                     : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
+    } else {
+        asm volatile("s_nop 1\n" MINIKV_ROW16("add") : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
+        if constexpr (N >= 32)
+            for (int i = 0; i < 4; i++) v[i] += __shfl_xor(v[i], 16);
+        if constexpr (N == 64)
+            for (int i = 0; i < 4; i++) v[i] += __shfl_xor(v[i], 32);
+    }
+}
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; exp2(-inf) = 0
 
 template <int N> struct Words { uint32_t v[N]; };
 template <int N> __device__ inline Words<N> load_words(const void *p)
@@ -128,19 +218,22 @@ __device__ void residual_chunk(const DecArgs &a, int u, int bq0, int nheads, int
         bool grow = false;
         float mn[kNH];
         for (int h = 0; h < kNH; h++) {
-            const float s = valid ? acc[h] * a.c1 : -INFINITY;
-            mn[h] = fmaxf(m[h], wave_max64(s));
+            acc[h] = valid ? acc[h] * a.c1 : -INFINITY;
+            mn[h] = acc[h];
+        }
+        wave_max64x4(mn);
+        for (int h = 0; h < kNH; h++) {
+            mn[h] = fmaxf(m[h], mn[h]);
             grow |= mn[h] > m[h];
-            acc[h] = s;
         }
         if (grow)
             for (int h = 0; h < kNH; h++) {
-                const float sc = exp2f(m[h] - mn[h]);
+                const float sc = fast_exp2(m[h] - mn[h]);
                 l[h] *= sc; o0[h] *= sc; o1[h] *= sc;
                 m[h] = mn[h];
             }
         for (int h = 0; h < kNH; h++) {
-            p[h] = exp2f(acc[h] - m[h]);
+            p[h] = fast_exp2(acc[h] - m[h]);
             l[h] += p[h];
             pw[h * 64 + lane] = p[h];
         }
@@ -164,11 +257,11 @@ __device__ void residual_chunk(const DecArgs &a, int u, int bq0, int nheads, int
     float *mo = reinterpret_cast<float *>(lds);            // [4 waves][kNH][128]
     float *mm = mo + 4 * kNH * kD;                         // [4][kNH]
     float *ml = mm + 4 * kNH;
+    wave_sum64x4(l);
     for (int h = 0; h < kNH; h++) {
         mo[(wave * kNH + h) * kD + 2 * lane] = o0[h];
         mo[(wave * kNH + h) * kD + 2 * lane + 1] = o1[h];
-        const float ls = wave_sum64(l[h]);
-        if (lane == 0) { mm[wave * kNH + h] = m[h]; ml[wave * kNH + h] = ls; }
+        if (lane == 0) { mm[wave * kNH + h] = m[h]; ml[wave * kNH + h] = l[h]; }
     }
     __syncthreads();
     const int c = tid & 127;
@@ -177,7 +270,7 @@ __device__ void residual_chunk(const DecArgs &a, int u, int bq0, int nheads, int
         for (int w = 0; w < 4; w++) M = fmaxf(M, mm[w * kNH + h]);
         float L = 0.f, O = 0.f;
         for (int w = 0; w < 4; w++) {
-            const float sc = exp2f(mm[w * kNH + h] - M);
+            const float sc = fast_exp2(mm[w * kNH + h] - M);
             L += ml[w * kNH + h] * sc;
             O += mo[(w * kNH + h) * kD + c] * sc;
         }
@@ -187,16 +280,72 @@ __device__ void residual_chunk(const DecArgs &a, int u, int bq0, int nheads, int
     }
 }
 
-// ------------------------------------------------------------------------------------------------
-template <int G, bool MFMA, bool LO>
-__global__ __launch_bounds__(256) void decode_tiled_kernel(DecArgs a)
+// The broadcast controls of the matrix instruction are immediates; these helpers turn the (unrolled,
+// hence constant) block index into one.
+#define MINIKV_MFMA_CASE(n) case n: acc = __builtin_amdgcn_mfma_f32_4x4x4f16(av, bv, acc, CB, n, 0); break;
+template <int CB>
+__device__ inline void mfma_bc(f4 &acc, h4 av, h4 bv, int abid)
 {
-    constexpr int NG = kPass / G > 0 ? kPass / G : 1;      // K groups per pass (G=128: 1)
-    constexpr int LPG = 64 / NG;                           // lanes per K group (= G/2)
-    constexpr int CPL = kD / LPG;                          // channels per lane in the table build
-    constexpr int NPR = CPL / 2;                           // channel pairs per lane
-    constexpr int NCG = kD / G;                            // V channel groups
-    constexpr int WAVE_HALFS = (LO ? 2 : 1) * NG * kQsG + NCG * kPsG;
+    switch (abid) {
+        MINIKV_MFMA_CASE(0) MINIKV_MFMA_CASE(1) MINIKV_MFMA_CASE(2) MINIKV_MFMA_CASE(3)
+        MINIKV_MFMA_CASE(4) MINIKV_MFMA_CASE(5) MINIKV_MFMA_CASE(6) MINIKV_MFMA_CASE(7)
+        MINIKV_MFMA_CASE(8) MINIKV_MFMA_CASE(9) MINIKV_MFMA_CASE(10) MINIKV_MFMA_CASE(11)
+        MINIKV_MFMA_CASE(12) MINIKV_MFMA_CASE(13) MINIKV_MFMA_CASE(14) MINIKV_MFMA_CASE(15)
+    }
+}
+template <int CB>
+__device__ inline void mfma_k(f4 &acc0, f4 &acc1, h4 av, h4 b0, h4 b1, int abid)
+{
+    mfma_bc<CB>(acc0, av, b0, abid);
+    mfma_bc<CB>(acc1, av, b1, abid);
+}
+template <int CB>
+__device__ inline void mfma_v(f4 &o0, f4 &o1, h4 a0, h4 a1, h4 b0, h4 b1, int abid)
+{
+    mfma_bc<CB>(o0, a0, b0, abid);
+    mfma_bc<CB>(o1, a1, b1, abid);
+}
+
+// ------------------------------------------------------------------------------------------------
+constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
+
+template <int N>
+__device__ inline float dpp_ror_add(float v)              // v + (v rotated right by N lanes inside its row of 16)
+{
+    return v + dpp_mov<0x120 + N>(0.f, v);
+}
+template <int H>
+__device__ inline float quad_bcast(float v)               // value of lane (4*(lane/4) + H)
+{
+    return dpp_mov<H * 0x55>(0.f, v);
+}
+
+// What one wave needs from global memory for the K half and the V half of one pass of 128 tokens.
+template <int NKW>
+struct KData {
+    u4 kw[4];               // K code words of tokens 2*lane (kw[0..1]) and 2*lane+1 (kw[2..3])
+    Words<NKW> ks, kz;      // this lane's bin of the K scale / zero row of its group
+};
+template <int NCG>
+struct VData {
+    u4 vw[2][2];            // V code words [channel lane / lane+64][64-token tile]: 4 blocks of 16 tokens each
+    Words<NCG> vs, vz;      // V scale / zero of tokens 2*lane and 2*lane+1 (zero when past the end)
+};
+
+template <int G, bool LO>
+__global__ __launch_bounds__(256, 2) void decode_tiled_kernel(DecArgs a)
+{
+    // K side: a K group spans G/2 token-lanes = BGK blocks of 4 lanes.  Block j of a group supplies the
+    // A operand (4 heads x 4 channels of q*Ks) of k-steps j, j+BGK, ...; the matrix instruction
+    // broadcasts it to the other blocks of the group (cbsz = log2 BGK, abid = j).
+    constexpr int BGK = G / 8, CBK = ilog2(BGK), NKR = 32 / BGK;
+    // V side: the lanes' channels lane, lane+64 share a channel group in runs of BGV blocks.
+    constexpr int BGV = G / 4 < 16 ? G / 4 : 16, CBV = ilog2(BGV), NVR = 32 / BGV;
+    constexpr int NCG = kD / G;
+    constexpr int NKW = NKR * 2;                           // words of one lane's slice of a K meta row
+    constexpr int WAVE_HALFS = NCG * kPsG;
+    typedef KData<NKW> KD;
+    typedef VData<NCG> VD;
 
     extern __shared__ __attribute__((aligned(16))) _Float16 lds[];
 
@@ -217,9 +366,7 @@ __global__ __launch_bounds__(256) void decode_tiled_kernel(DecArgs a)
     const int t_end = min(T, t_begin + a.chunk);
     if (t_begin >= t_end) return;
 
-    _Float16 *qs_hi = lds + wave * WAVE_HALFS;
-    _Float16 *qs_lo = qs_hi + NG * kQsG;                   // only used when LO
-    _Float16 *ps = qs_hi + (LO ? 2 : 1) * NG * kQsG;
+    _Float16 *ps = lds + wave * WAVE_HALFS;
 
     const uint32_t *Kc = a.Kc + (size_t)u * kc_words(a.Tcap);
     const uint32_t *Vc = a.Vc + (size_t)u * vc_words(a.Tcap);
@@ -228,28 +375,36 @@ __global__ __launch_bounds__(256) void decode_tiled_kernel(DecArgs a)
     const uint16_t *Vs = a.Vs + (size_t)u * a.Tcap * NCG;
     const uint16_t *Vz = a.Vz + (size_t)u * a.Tcap * NCG;
 
-    // ---- per-lane constants of the table build: this lane's CPL channels of every head's query
-    const int gl = lane / LPG;                             // K group (of the pass) this lane serves AND
-                                                           // the group of its own two tokens
-    const int c0 = (lane % LPG) * CPL;                     // first channel of the lane's slice
-    h2 qraw[kNH][NPR], qscl[kNH][NPR];
+    const int blk4 = lane >> 2, row = lane & 3;            // block of 4 lanes; row = query head this lane
+                                                           // supplies as A operand
+    const int gl = blk4 / BGK;                             // K group (of the pass) of this lane's tokens
+    const int bbk = blk4 % BGK;                            // this lane's bin of k-steps: bbk, bbk+BGK, ...
+    const int bbv = blk4 % BGV;                            // same on the V side (k-steps of 4 tokens)
+
+    // ---- this lane's query values: head `row`, the channels of its k-steps, raw and pre-scaled by the
+    // 4^-j of the code field (channel pair (c, c+1), c even, is field j = (c % 16) / 2 of its K word)
+    h2 qraw[NKR][2], qscl[NKR][2];
 #pragma unroll
-    for (int h = 0; h < kNH; h++)
+    for (int i = 0; i < NKR; i++)
 #pragma unroll
-        for (int p = 0; p < NPR; p++) {
+        for (int ep = 0; ep < 2; ep++) {
+            const int c = 4 * (bbk + BGK * i) + 2 * ep;
             uint32_t bits = 0;
-            if (h < nheads) bits = *reinterpret_cast<const uint32_t *>(a.q + (size_t)(bq0 + h) * kD + c0 + 2 * p);
-            qraw[h][p] = as_h2(bits);
-            // channel pair (c, c+1), c even, sits in field j = (c % 16) / 2 of its K word
-            const float sc = fld_scale(((c0 + 2 * p) & 15) >> 1);
-            qscl[h][p] = qraw[h][p] * (_Float16)sc;
+            if (row < nheads) bits = *reinterpret_cast<const uint32_t *>(a.q + (size_t)(bq0 + row) * kD + c);
+            qraw[i][ep] = as_h2(bits);
+            qscl[i][ep] = qraw[i][ep] * (_Float16)fld_scale((c & 15) >> 1);
         }
 
     // V side: this lane's two channels and their channel groups
     const int cg0 = lane / G;                              // G=128: 0
     const int cg1 = (lane + 64) / G;
+    // Tokens 2*lane, 2*lane+1 are field j = lane & 7 of their V word.  The weights of this lane carry the
+    // constant factor 2^lg = 16 * 4^-shift so that the masked V field needs no shift; the lane's running
+    // sums l and oz carry the same factor and are unscaled once at the end.
+    const float lg = 4.0f - (float)fld_shift(lane & 7);
+    const float unlg = fast_exp2(-lg);
 
-    float m[kNH], l_lane[kNH];
+    float m[kNH], l_lane[kNH];                             // m is wave-uniform
     f4 O0 = {0.f, 0.f, 0.f, 0.f}, O1 = {0.f, 0.f, 0.f, 0.f};   // channel lane / lane+64, 4 heads each
     float oz[kNH][NCG];
 #pragma unroll
@@ -262,123 +417,104 @@ __global__ __launch_bounds__(256) void decode_tiled_kernel(DecArgs a)
     const float kscale = a.c1 * 16777216.0f;               // undo the 2^-24 of the subnormal code fields
     const int npass = (t_end - t_begin + kPass - 1) / kPass;
 
-    for (int pass = wave; pass < npass; pass += 4) {
-        const int tp = t_begin + pass * kPass;             // multiple of 128
-        const bool valid = tp + 2 * lane < t_end;          // both tokens of the lane (t_end % 16 == 0)
-
-        // ---------------- loads of the pass
+    auto load_k = [&](int tp) -> KD {
+        KD d;
         const u4 *ktile = reinterpret_cast<const u4 *>(Kc + (size_t)(tp >> 7) * 1024);
-        u4 kw[4];
 #pragma unroll
-        for (int i = 0; i < 4; i++) kw[i] = ktile[i * 64 + lane];
+        for (int i = 0; i < 4; i++) d.kw[i] = ktile[i * 64 + lane];
+        const bool gvalid = tp + gl * G < t_end;
+        const size_t go = ((size_t)(tp / G) + (gvalid ? gl : 0)) * kD + bbk * (NKR * 4);
+        d.ks = load_words<NKW>(Ks + go);
+        d.kz = load_words<NKW>(Kz + go);
+        return d;
+    };
+    auto load_v = [&](int tp) -> VD {
+        VD d;
         const u4 *vtile = reinterpret_cast<const u4 *>(Vc + (size_t)(tp >> 6) * (4 * kD));
-        u4 vw[2][2];                                       // [channel half][64-token tile]
 #pragma unroll
         for (int tl = 0; tl < 2; tl++) {
-            vw[0][tl] = vtile[tl * kD + lane];
-            vw[1][tl] = vtile[tl * kD + lane + 64];
+            d.vw[0][tl] = vtile[tl * kD + lane];
+            d.vw[1][tl] = vtile[tl * kD + lane + 64];
         }
-        const bool gvalid = tp + gl * G < t_end;
-        Words<NPR> ksw, kzw;
-        {
-            const size_t go = ((size_t)(tp / G) + (gvalid ? gl : 0)) * kD + c0;
-            ksw = load_words<NPR>(Ks + go);
-            kzw = load_words<NPR>(Kz + go);
-        }
-        Words<NCG> vsw, vzw;                               // 2 tokens x NCG fp16 = NCG words
-        {
-            const size_t vo = (size_t)(valid ? tp + 2 * lane : tp) * NCG;
-            vsw = load_words<NCG>(Vs + vo);
-            vzw = load_words<NCG>(Vz + vo);
-        }
+        // past the end the (clamped) load still happens and the value is masked to zero afterwards, so
+        // that the number of loads in flight is the same on every path
+        const bool valid = tp + 2 * lane < t_end;
+        const size_t vo = (size_t)(valid ? tp + 2 * lane : tp) * NCG;
+        d.vs = load_words<NCG>(Vs + vo);
+        d.vz = load_words<NCG>(Vz + vo);
+        return d;
+    };
 
-        // ---------------- qs table of the pass's K groups, and qz = sum_c q_c Kz[g,c]
-        float qz[kNH] = {0.f, 0.f, 0.f, 0.f};
+    float s0[kNH], s1[kNH];                                // scores of the lane's two tokens (K phase -> V phase)
+
+    // ---------------- K phase: scores of tokens 2*lane, 2*lane+1 for the 4 heads
+    auto k_phase = [&](const KD &d, int tp) {
+        const bool valid = tp + 2 * lane < t_end;          // both tokens of the lane (t_end % 16 == 0)
+        // A operands of this lane's k-steps (exact hi + lo split of q * Ks), and qz = sum_c q_c Kz[g,c]
+        h4 a_hi[NKR], a_lo[NKR];
+        float qz = 0.f;
 #pragma unroll
-        for (int p = 0; p < NPR; p++) {
-            const h2 ks2 = as_h2(ksw.v[p]), kz2 = as_h2(kzw.v[p]);
-            const int c = c0 + 2 * p;                      // even channel of the pair
-            const int off = gl * kQsG + (c >> 2) * 16 + (c & 3);
+        for (int i = 0; i < NKR; i++) {
+            h2 hi[2], lo[2];
 #pragma unroll
-            for (int h = 0; h < kNH; h++) {
-                const h2 hi = qscl[h][p] * ks2;
-                *reinterpret_cast<h2 *>(qs_hi + off + h * 4) = hi;
-                if constexpr (LO) {
-                    const h2 lo = __builtin_elementwise_fma(qscl[h][p], ks2, -hi);
-                    *reinterpret_cast<h2 *>(qs_lo + off + h * 4) = lo;
-                }
-                qz[h] = __builtin_amdgcn_fdot2(qraw[h][p], kz2, qz[h], false);
+            for (int ep = 0; ep < 2; ep++) {
+                const h2 ks2 = as_h2(d.ks.v[2 * i + ep]), kz2 = as_h2(d.kz.v[2 * i + ep]);
+                hi[ep] = qscl[i][ep] * ks2;
+                if constexpr (LO) lo[ep] = __builtin_elementwise_fma(qscl[i][ep], ks2, -hi[ep]);
+                qz = __builtin_amdgcn_fdot2(qraw[i][ep], kz2, qz, false);
             }
+            a_hi[i] = h4{hi[0][0], hi[0][1], hi[1][0], hi[1][1]};
+            if constexpr (LO) a_lo[i] = h4{lo[0][0], lo[0][1], lo[1][0], lo[1][1]};
         }
-#pragma unroll
-        for (int h = 0; h < kNH; h++)
-            for (int o = LPG / 2; o; o >>= 1) qz[h] += __shfl_xor(qz[h], o);
-        __builtin_amdgcn_wave_barrier();
+        // sum the partial qz of the BGK blocks of the group (same row, lanes 4 apart)
+        if constexpr (BGK == 2) qz += __shfl_xor(qz, 4);
+        if constexpr (BGK >= 4) { qz = dpp_ror_add<4>(qz); qz = dpp_ror_add<8>(qz); }
+        if constexpr (BGK >= 8) qz += __shfl_xor(qz, 16);
+        if constexpr (BGK >= 16) qz += __shfl_xor(qz, 32);
 
-        // ---------------- K products: scores of tokens 2*lane, 2*lane+1 for the 4 heads
         f4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-        {
-            const _Float16 *th = qs_hi + gl * kQsG;
-            const _Float16 *tl = qs_lo + gl * kQsG;
 #pragma unroll
-            for (int w = 0; w < 8; w++) {
-                const uint32_t w0 = kw[w >> 2][w & 3], w1 = kw[2 + (w >> 2)][w & 3];
-                const uint32_t w0s = w0 >> 6, w1s = w1 >> 6;
+        for (int w = 0; w < 8; w++) {
+            const uint32_t w0 = d.kw[w >> 2][w & 3], w1 = d.kw[2 + (w >> 2)][w & 3];
+            const uint32_t w0s = w0 >> 6, w1s = w1 >> 6;
 #pragma unroll
-                for (int sq = 0; sq < 4; sq++) {
-                    const int s = 4 * w + sq;
-                    const h2 x00 = field(w0, w0s, 2 * sq), x01 = field(w0, w0s, 2 * sq + 1);
-                    const h2 x10 = field(w1, w1s, 2 * sq), x11 = field(w1, w1s, 2 * sq + 1);
-                    if constexpr (MFMA) {
-                        const h4 b0 = {x00[0], x00[1], x01[0], x01[1]};
-                        const h4 b1 = {x10[0], x10[1], x11[0], x11[1]};
-                        const h4 ah = *reinterpret_cast<const h4 *>(th + s * 16 + (lane & 3) * 4);
-                        acc0 = __builtin_amdgcn_mfma_f32_4x4x4f16(ah, b0, acc0, 0, 0, 0);
-                        acc1 = __builtin_amdgcn_mfma_f32_4x4x4f16(ah, b1, acc1, 0, 0, 0);
-                        if constexpr (LO) {
-                            const h4 al = *reinterpret_cast<const h4 *>(tl + s * 16 + (lane & 3) * 4);
-                            acc0 = __builtin_amdgcn_mfma_f32_4x4x4f16(al, b0, acc0, 0, 0, 0);
-                            acc1 = __builtin_amdgcn_mfma_f32_4x4x4f16(al, b1, acc1, 0, 0, 0);
-                        }
-                    } else {
-#pragma unroll
-                        for (int h = 0; h < kNH; h++) {
-                            const u4 ah = *reinterpret_cast<const u4 *>(th + s * 16 + h * 4 - 4 * (h & 1)) ;
-                            // two heads share one 128-bit read: (h even: words 0,1 ; h odd: words 2,3)
-                            const h2 a0 = as_h2(ah[2 * (h & 1)]), a1 = as_h2(ah[2 * (h & 1) + 1]);
-                            acc0[h] = __builtin_amdgcn_fdot2(a0, x00, acc0[h], false);
-                            acc0[h] = __builtin_amdgcn_fdot2(a1, x01, acc0[h], false);
-                            acc1[h] = __builtin_amdgcn_fdot2(a0, x10, acc1[h], false);
-                            acc1[h] = __builtin_amdgcn_fdot2(a1, x11, acc1[h], false);
-                            if constexpr (LO) {
-                                const u4 al = *reinterpret_cast<const u4 *>(tl + s * 16 + h * 4 - 4 * (h & 1));
-                                const h2 l0 = as_h2(al[2 * (h & 1)]), l1 = as_h2(al[2 * (h & 1) + 1]);
-                                acc0[h] = __builtin_amdgcn_fdot2(l0, x00, acc0[h], false);
-                                acc0[h] = __builtin_amdgcn_fdot2(l1, x01, acc0[h], false);
-                                acc1[h] = __builtin_amdgcn_fdot2(l0, x10, acc1[h], false);
-                                acc1[h] = __builtin_amdgcn_fdot2(l1, x11, acc1[h], false);
-                            }
-                        }
-                    }
-                }
+            for (int sq = 0; sq < 4; sq++) {
+                const int s = 4 * w + sq;                  // k-step: channels 4s..4s+3
+                const h2 x00 = field(w0, w0s, 2 * sq), x01 = field(w0, w0s, 2 * sq + 1);
+                const h2 x10 = field(w1, w1s, 2 * sq), x11 = field(w1, w1s, 2 * sq + 1);
+                const h4 b0 = {x00[0], x00[1], x01[0], x01[1]};
+                const h4 b1 = {x10[0], x10[1], x11[0], x11[1]};
+                mfma_k<CBK>(acc0, acc1, a_hi[s / BGK], b0, b1, s % BGK);
+                if constexpr (LO) mfma_k<CBK>(acc0, acc1, a_lo[s / BGK], b0, b1, s % BGK);
             }
         }
-
-        // ---------------- online softmax (per head, wave-wide maximum)
-        float s0[kNH], s1[kNH], mn[kNH];
-        bool grow = false;
+        const float z0 = quad_bcast<0>(qz) * a.c1, z1 = quad_bcast<1>(qz) * a.c1;
+        const float z2 = quad_bcast<2>(qz) * a.c1, z3 = quad_bcast<3>(qz) * a.c1;
+        const float zz[kNH] = {z0, z1, z2, z3};
 #pragma unroll
         for (int h = 0; h < kNH; h++) {
-            const float zz = qz[h] * a.c1;
-            s0[h] = valid ? acc0[h] * kscale + zz : -INFINITY;
-            s1[h] = valid ? acc1[h] * kscale + zz : -INFINITY;
-            mn[h] = fmaxf(m[h], wave_max64(fmaxf(s0[h], s1[h])));
+            s0[h] = valid ? acc0[h] * kscale + zz[h] : -INFINITY;
+            s1[h] = valid ? acc1[h] * kscale + zz[h] : -INFINITY;
+        }
+    };
+
+    // ---------------- softmax update, ps table, V products
+    auto v_phase = [&](const VD &d, int tp) {
+        const bool valid = tp + 2 * lane < t_end;
+        float mn[kNH];
+        bool grow = false;
+#pragma unroll
+        for (int h = 0; h < kNH; h++) mn[h] = fmaxf(s0[h], s1[h]);
+        wave_max64x4(mn);
+#pragma unroll
+        for (int h = 0; h < kNH; h++) {
+            mn[h] = fmaxf(m[h], mn[h]);
             grow |= mn[h] > m[h];
         }
-        if (grow) {
+        if (grow) {                                        // wave-uniform
 #pragma unroll
             for (int h = 0; h < kNH; h++) {
-                const float sc = exp2f(m[h] - mn[h]);
+                const float sc = fast_exp2(m[h] - mn[h]);
                 l_lane[h] *= sc;
                 O0[h] *= sc;
                 O1[h] *= sc;
@@ -387,82 +523,96 @@ __global__ __launch_bounds__(256) void decode_tiled_kernel(DecArgs a)
                 m[h] = mn[h];
             }
         }
-
-        // ---------------- weights, ps table, zero-point term
         {
-            // token 2*lane is field j = lane & 7 of its V word (low half), 2*lane+1 the high half
-            const float vsc = 16.0f * fld_scale(lane & 7);
+            // (vs, vz) words hold [token 2l: NCG halfs][token 2l+1: NCG halfs]; pair them per channel group
+            h2 vsp[NCG], vzp[NCG];
+#pragma unroll
+            for (int g = 0; g < NCG; g++) {
+                const int i0 = g, i1 = NCG + g;            // half index of (token 0, g) and (token 1, g)
+                const uint32_t sel = ((i0 & 1) ? 0x00000302u : 0x00000100u) | ((i1 & 1) ? 0x07060000u : 0x05040000u);
+                const uint32_t sv = __builtin_amdgcn_perm(d.vs.v[i1 >> 1], d.vs.v[i0 >> 1], sel);
+                const uint32_t zv = __builtin_amdgcn_perm(d.vz.v[i1 >> 1], d.vz.v[i0 >> 1], sel);
+                vsp[g] = as_h2(valid ? sv : 0u);
+                vzp[g] = as_h2(valid ? zv : 0u);
+            }
 #pragma unroll
             for (int h = 0; h < kNH; h++) {
-                const float p0 = exp2f(s0[h] - m[h]), p1 = exp2f(s1[h] - m[h]);   // masked lanes: 0
+                const float mo = m[h] - lg;
+                const float p0 = fast_exp2(s0[h] - mo), p1 = fast_exp2(s1[h] - mo);   // masked lanes: 0
                 l_lane[h] += p0 + p1;
+                const h2 ph = {(_Float16)p0, (_Float16)p1};
 #pragma unroll
                 for (int g = 0; g < NCG; g++) {
-                    // words hold [token 2l: NCG halfs][token 2l+1: NCG halfs]
-                    const int i0 = g, i1 = NCG + g;
-                    const h2 sw0 = as_h2(vsw.v[i0 >> 1]), sw1 = as_h2(vsw.v[i1 >> 1]);
-                    const h2 zw0 = as_h2(vzw.v[i0 >> 1]), zw1 = as_h2(vzw.v[i1 >> 1]);
-                    const float vs0 = valid ? (float)sw0[i0 & 1] : 0.f, vs1 = valid ? (float)sw1[i1 & 1] : 0.f;
-                    const float vz0 = valid ? (float)zw0[i0 & 1] : 0.f, vz1 = valid ? (float)zw1[i1 & 1] : 0.f;
-                    const h2 pv = {(_Float16)(p0 * vs0 * vsc), (_Float16)(p1 * vs1 * vsc)};
-                    *reinterpret_cast<h2 *>(ps + g * kPsG + h * kPsH + 2 * lane) = pv;
-                    oz[h][g] += p0 * vz0 + p1 * vz1;
+                    *reinterpret_cast<h2 *>(ps + g * kPsG + h * kPsH + 2 * lane) = ph * vsp[g];
+                    oz[h][g] = __builtin_amdgcn_fdot2(ph, vzp[g], oz[h][g], false);
                 }
             }
         }
         __builtin_amdgcn_wave_barrier();
 
-        // ---------------- V products: channels lane and lane+64, 4 heads, 4 tokens per step
-        {
-            const _Float16 *pa0 = ps + cg0 * kPsG + (MFMA ? (lane & 3) * kPsH : 0);
-            const _Float16 *pa1 = ps + cg1 * kPsG + (MFMA ? (lane & 3) * kPsH : 0);
+        // A operands of this lane's V k-steps (4 tokens each): ps[channel group][head row][tokens]
+        h4 a0[NVR], a1[NVR];
 #pragma unroll
-            for (int blk = 0; blk < 8; blk++) {
-                const uint32_t v0 = vw[0][blk >> 2][blk & 3], v1 = vw[1][blk >> 2][blk & 3];
-                const uint32_t v0s = v0 >> 6, v1s = v1 >> 6;
+        for (int i = 0; i < NVR; i++) {
+            const int tok = 4 * (bbv + BGV * i);
+            a0[i] = *reinterpret_cast<const h4 *>(ps + cg0 * kPsG + row * kPsH + tok);
+            a1[i] = *reinterpret_cast<const h4 *>(ps + cg1 * kPsG + row * kPsH + tok);
+        }
 #pragma unroll
-                for (int ks = 0; ks < 4; ks++) {
-                    const int tok = 16 * blk + 4 * ks;
-                    const h2 x00 = field(v0, v0s, 2 * ks), x01 = field(v0, v0s, 2 * ks + 1);
-                    const h2 x10 = field(v1, v1s, 2 * ks), x11 = field(v1, v1s, 2 * ks + 1);
-                    if constexpr (MFMA) {
-                        const h4 b0 = {x00[0], x00[1], x01[0], x01[1]};
-                        const h4 b1 = {x10[0], x10[1], x11[0], x11[1]};
-                        const h4 a0 = *reinterpret_cast<const h4 *>(pa0 + tok);
-                        const h4 a1 = *reinterpret_cast<const h4 *>(pa1 + tok);
-                        O0 = __builtin_amdgcn_mfma_f32_4x4x4f16(a0, b0, O0, 0, 0, 0);
-                        O1 = __builtin_amdgcn_mfma_f32_4x4x4f16(a1, b1, O1, 0, 0, 0);
-                    } else {
+        for (int blk = 0; blk < 8; blk++) {
+            const uint32_t v0 = d.vw[0][blk >> 2][blk & 3], v1 = d.vw[1][blk >> 2][blk & 3];
+            const uint32_t v0s = v0 >> 6, v1s = v1 >> 6;
 #pragma unroll
-                        for (int h = 0; h < kNH; h++) {
-                            const h4 a0 = *reinterpret_cast<const h4 *>(pa0 + h * kPsH + tok);
-                            const h4 a1 = *reinterpret_cast<const h4 *>(pa1 + h * kPsH + tok);
-                            const h2 a00 = {a0[0], a0[1]}, a01 = {a0[2], a0[3]};
-                            const h2 a10 = {a1[0], a1[1]}, a11 = {a1[2], a1[3]};
-                            O0[h] = __builtin_amdgcn_fdot2(a00, x00, O0[h], false);
-                            O0[h] = __builtin_amdgcn_fdot2(a01, x01, O0[h], false);
-                            O1[h] = __builtin_amdgcn_fdot2(a10, x10, O1[h], false);
-                            O1[h] = __builtin_amdgcn_fdot2(a11, x11, O1[h], false);
-                        }
-                    }
-                }
+            for (int kq = 0; kq < 4; kq++) {
+                const int ks = 4 * blk + kq;               // k-step: tokens 4ks..4ks+3 of the pass
+                const h2 x00 = field(v0, v0s, 2 * kq), x01 = field(v0, v0s, 2 * kq + 1);
+                const h2 x10 = field(v1, v1s, 2 * kq), x11 = field(v1, v1s, 2 * kq + 1);
+                const h4 b0 = {x00[0], x00[1], x01[0], x01[1]};
+                const h4 b1 = {x10[0], x10[1], x11[0], x11[1]};
+                mfma_v<CBV>(O0, O1, a0[ks / BGV], a1[ks / BGV], b0, b1, ks % BGV);
             }
         }
         __builtin_amdgcn_wave_barrier();
+    };
+
+    // ---------------- the wave's passes.  Loads run one phase ahead of their use and are issued on every
+    // path (the last iteration re-requests its own tile), so the count in flight is always the same.
+    if (wave < npass) {
+        const int cnt = (npass - wave + 3) >> 2;           // passes wave, wave+4, ... of this wave
+        auto tp_of = [&](int i) { return t_begin + (wave + 4 * (i < cnt ? i : cnt - 1)) * kPass; };
+        KD kd = load_k(tp_of(0));
+        VD vd = load_v(tp_of(0));
+        for (int i = 0; i < cnt; i++) {
+            const int tp = tp_of(i);
+            k_phase(kd, tp);
+            kd = load_k(tp_of(i + 1));
+            v_phase(vd, tp);
+            vd = load_v(tp_of(i + 1));
+        }
     }
 
     // ---------------- finish the wave: undo operand scalings, add the zero-point term
     const float vun = 16777216.0f / 16.0f;                 // 2^24 (subnormal fields) / 2^4 (ps headroom)
     float lsum[kNH];
 #pragma unroll
+    for (int h = 0; h < kNH; h++) lsum[h] = l_lane[h] * unlg;
+    wave_sum64x4(lsum);
+#pragma unroll
+    for (int g = 0; g < NCG; g++) {
+        float zs[kNH];
+#pragma unroll
+        for (int h = 0; h < kNH; h++) zs[h] = oz[h][g] * unlg;
+        wave_sum64x4(zs);
+#pragma unroll
+        for (int h = 0; h < kNH; h++) oz[h][g] = zs[h];    // now the wave total (uniform)
+    }
+#pragma unroll
     for (int h = 0; h < kNH; h++) {
-        lsum[h] = wave_sum64(l_lane[h]);
         float z0 = 0.f, z1 = 0.f;
 #pragma unroll
         for (int g = 0; g < NCG; g++) {
-            const float zs = wave_sum64(oz[h][g]);
-            z0 = (g == cg0) ? zs : z0;
-            z1 = (g == cg1) ? zs : z1;
+            z0 = (g == cg0) ? oz[h][g] : z0;
+            z1 = (g == cg1) ? oz[h][g] : z1;
         }
         O0[h] = O0[h] * vun + z0;
         O1[h] = O1[h] * vun + z1;
@@ -486,7 +636,7 @@ __global__ __launch_bounds__(256) void decode_tiled_kernel(DecArgs a)
         for (int w = 0; w < 4; w++) M = fmaxf(M, mm[w * kNH + h]);
         float L = 0.f, O = 0.f;
         for (int w = 0; w < 4; w++) {
-            const float sc = exp2f(mm[w * kNH + h] - M);
+            const float sc = fast_exp2(mm[w * kNH + h] - M);
             L += ml[w * kNH + h] * sc;
             O += mo[(w * kNH + h) * kD + c] * sc;
         }
@@ -496,45 +646,41 @@ __global__ __launch_bounds__(256) void decode_tiled_kernel(DecArgs a)
     }
 }
 
-template <int G, bool MFMA, bool LO>
+template <int G, bool LO>
 static int launch_tiled(const DecArgs &a, int units, hipStream_t st)
 {
-    constexpr int NG = kPass / G > 0 ? kPass / G : 1;
     constexpr int NCG = kD / G;
-    constexpr int WAVE_HALFS = (LO ? 2 : 1) * NG * kQsG + NCG * kPsG;
+    constexpr int WAVE_HALFS = NCG * kPsG;
     constexpr size_t merge_bytes = (size_t)(4 * kNH * kD + 8 * kNH) * sizeof(float);
     constexpr size_t res_bytes = (size_t)kNH * kD * 2 + 4 * kNH * 64 * sizeof(float);
     size_t lds_bytes = (size_t)4 * WAVE_HALFS * 2;
     if (lds_bytes < merge_bytes) lds_bytes = merge_bytes;
     if (lds_bytes < res_bytes) lds_bytes = res_bytes;
-    auto kern = decode_tiled_kernel<G, MFMA, LO>;
-    static bool attr_set = false;                          // per instantiation
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds_bytes) != hipSuccess)
-            return MINIKV_ELAUNCH;
-        attr_set = true;
-    }
+    auto kern = decode_tiled_kernel<G, LO>;
     dim3 grid(a.nchunk + 1, units, (a.rep + kNH - 1) / kNH);
     hipLaunchKernelGGL(kern, grid, dim3(256), lds_bytes, st, a);
     return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
 }
 
-template <bool MFMA>
+template <bool LO>
 static int launch_tiled_g(const DecArgs &a, int G, int units, hipStream_t st)
 {
     switch (G) {
-    case 16: return launch_tiled<16, MFMA, true>(a, units, st);
-    case 32: return launch_tiled<32, MFMA, true>(a, units, st);
-    case 64: return launch_tiled<64, MFMA, true>(a, units, st);
-    case 128: return launch_tiled<128, MFMA, true>(a, units, st);
+    case 16: return launch_tiled<16, LO>(a, units, st);
+    case 32: return launch_tiled<32, LO>(a, units, st);
+    case 64: return launch_tiled<64, LO>(a, units, st);
+    case 128: return launch_tiled<128, LO>(a, units, st);
     }
     return MINIKV_EUNSUPPORTED;
 }
 
-int launch_decode_tiled(const DecArgs &a, int G, int units, bool mfma, hipStream_t st)
+int launch_decode_tiled(const DecArgs &a, int G, int units, int variant, hipStream_t st)
 {
-    return mfma ? launch_tiled_g<true>(a, G, units, st) : launch_tiled_g<false>(a, G, units, st);
+    switch (variant) {
+    case 3: return launch_tiled_g<true>(a, G, units, st);
+    case 4: return launch_tiled_g<false>(a, G, units, st);
+    }
+    return MINIKV_EINVAL;
 }
 
 }  // namespace minikv

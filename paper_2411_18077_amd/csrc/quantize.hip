@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
         }
         uint16_t sh, zh; float inv, zf;
         group_params(mn, mx, sh, zh, inv, zf);
-        const size_t o = ((size_t)u * (a.Tcap / G) + (size_t)(t0 / G + g)) * kD + c;
+        const size_t o = ((size_t)u * (a.Tcap / G) + (size_t)(t0 / G + g)) * kD + k_meta_pos(G, c);
         a.Ks[o] = sh;
         a.Kz[o] = zh;
         p_inv[gi] = inv;

@@ -29,3 +29,17 @@ def k_word_index(t, c):
 def v_word_index(t, c, D=128):
     tile, tau = t // 64, t % 64
     return tile * 4 * D + c * 4 + tau // 16, 16 * (tau % 2) + 2 * ((tau % 16) // 2)
+
+
+def k_meta_pos(G, c):
+    """Hand-written restatement of the documented position of channel c in a K scale / zero row."""
+    nb, q = G // 8, c // 4
+    return ((q % nb) * (32 // nb) + q // nb) * 4 + c % 4
+
+
+def k_meta_natural(ref, a, G):
+    """K scale / zero rows [.., D] re-ordered to natural channel order."""
+    perm = np.array([k_meta_pos(G, c) for c in range(a.shape[-1])])
+    assert np.array_equal(perm, ref.k_meta_perm(G))
+    assert sorted(perm.tolist()) == list(range(a.shape[-1]))
+    return a[..., perm]

@@ -74,5 +74,5 @@ def test_pointer_and_workspace_checks(api):
     assert l.kv_quantize_pack(C.byref(s), P(0x1000), P(0x1000), 64, None, 0, P(0x1000), 512, C.byref(good), None) == -1
     assert l.kv_quantize_pack(C.byref(s), P(0x1000), P(0x1000), 64, P(0x1000), 16, P(0x1000), 32, C.byref(good), None) == -1
     assert l.kv_quantize_pack(C.byref(s), P(0x1000), P(0x1000), 64, None, 0, P(0x1000), 0, C.byref(good), None) == 0
-    assert l.minikv_set_variant(99) == -1 and l.minikv_set_variant(0) == 0
+    assert l.minikv_set_variant(99) == -1 and l.minikv_set_variant(2) == -1 and l.minikv_set_variant(0) == 0
     assert b"workspace" in l.minikv_strerror(-3)

@@ -7,7 +7,7 @@ closed form, an fp64 arg-min over the four levels with ties listed explicitly, a
 import numpy as np
 import pytest
 
-from helpers import ref_cache_from
+from helpers import ref_cache_from, k_meta_natural
 
 
 def _rand(U, L, D, seed, scale=1.0):
@@ -25,7 +25,7 @@ def test_round_trip_half_step_and_end_codes(ref, G):
     for u in range(U):
         kc, vc = ref.unpack_codes(c, u)
         kh, vh = ref.dequant(c, u)
-        ks = np.repeat(c.Ks[u, : L // G].astype(np.float64), G, axis=0)          # [L, D]
+        ks = np.repeat(k_meta_natural(ref, c.Ks[u, : L // G], G).astype(np.float64), G, axis=0)          # [L, D]
         vs = np.repeat(c.Vs[u, :L].astype(np.float64), G, axis=1)                # [L, D]
         # |x - x_hat| <= (stored step)/2, up to the three binary32 roundings inside the code decision
         assert np.all(np.abs(K[u].astype(np.float64) - kh) <= ks * 0.5 * (1 + 2.0 ** -18))
@@ -37,7 +37,7 @@ def test_round_trip_half_step_and_end_codes(ref, G):
         vg = vc.reshape(L, D // G, G)
         assert np.all(vg.min(axis=2) == 0) and np.all(vg.max(axis=2) == 3)
         # zero-point is the group minimum itself
-        assert np.array_equal(c.Kz[u, : L // G], K[u].reshape(L // G, G, D).min(axis=1))
+        assert np.array_equal(k_meta_natural(ref, c.Kz[u, : L // G], G), K[u].reshape(L // G, G, D).min(axis=1))
         assert np.array_equal(c.Vz[u, :L], V[u].reshape(L, D // G, G).min(axis=2))
         xmin = K[u].reshape(L // G, G, D).astype(np.float64)
         at_min = xmin == xmin.min(axis=1, keepdims=True)
@@ -64,7 +64,7 @@ def test_lattice_is_lossless_with_known_codes(ref, G):
     kh, vh = ref.dequant(c, 0)
     assert np.array_equal(kc, lev_k[0]) and np.array_equal(vc, lev_v[0])
     assert np.array_equal(kh, K[0]) and np.array_equal(vh, V[0])
-    assert np.array_equal(c.Ks[0, : L // G].astype(np.float64), s_k[0, :, 0, :])
+    assert np.array_equal(k_meta_natural(ref, c.Ks[0, : L // G], G).astype(np.float64), s_k[0, :, 0, :])
     assert np.array_equal(c.Vz[0, :L].astype(np.float64), z_v[0, :, :, 0])
 
 
@@ -78,7 +78,8 @@ def test_codes_are_the_nearest_level_in_fp64(ref):
     for u in range(U):
         kc, vc = ref.unpack_codes(c, u)
         for x, codes, s, z in (
-            (K[u], kc, np.repeat(c.Ks[u, : L // G], G, axis=0), np.repeat(c.Kz[u, : L // G], G, axis=0)),
+            (K[u], kc, np.repeat(k_meta_natural(ref, c.Ks[u, : L // G], G), G, axis=0),
+             np.repeat(k_meta_natural(ref, c.Kz[u, : L // G], G), G, axis=0)),
             (V[u], vc, np.repeat(c.Vs[u, :L], G, axis=1), np.repeat(c.Vz[u, :L], G, axis=1)),
         ):
             x, s, z = x.astype(np.float64), s.astype(np.float64), z.astype(np.float64)
@@ -104,7 +105,7 @@ def test_hand_worked_ties_round_half_to_even(ref):
     kc, vc = ref.unpack_codes(c, 0)
     assert kc[:16, 3].tolist() == want
     assert vc[7, :16].tolist() == want
-    assert float(c.Ks[0, 0, 3]) == 1.0 and float(c.Kz[0, 0, 3]) == 0.0
+    assert float(k_meta_natural(ref, c.Ks[0, 0], G)[3]) == 1.0 and float(k_meta_natural(ref, c.Kz[0, 0], G)[3]) == 0.0
 
 
 def test_degenerate_group_and_negative_zero(ref):
