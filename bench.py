@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--max-copies", type=int, default=0, help="cap on distinct cache copies (0: steps+warmup)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference dispatches for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -111,6 +114,14 @@ def main():
         c = copies[i % ncopy]
         api.kv_append_residual(shape, c["k_new"], c["v_new"], c["cache"])
         api.minikv_decode_attn(shape, c["q"], c["cache"], sm, c["out"])
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.int32, device=dev).fill_(1)     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------------ timed region
     for i in range(args.warmup):

@@ -332,6 +332,13 @@ struct VData {
     Words<NCG> vs, vz;      // V scale / zero of tokens 2*lane and 2*lane+1 (zero when past the end)
 };
 
+#ifdef MINIKV_TIMELINE
+__device__ long long g_timeline[16384 * 8];
+#define TL(slot) do { if (tid == 0) g_timeline[(size_t)((blockIdx.y * gridDim.x + blockIdx.x) % 16384) * 8 + (slot)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define TL(slot) do {} while (0)
+#endif
+
 template <int G, bool LO>
 __global__ __launch_bounds__(256, 2) void decode_tiled_kernel(DecArgs a)
 {
@@ -354,17 +361,23 @@ __global__ __launch_bounds__(256, 2) void decode_tiled_kernel(DecArgs a)
     const int b = u / a.Hkv, kvh = u % a.Hkv;
     const int bq0 = b * a.Hq + kvh * a.rep + hs * kNH;
     const int nheads = min(kNH, a.rep - hs * kNH);
+    TL(0);
+#ifdef MINIKV_TIMELINE
+    if (tid == 0) { unsigned id; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(id)); g_timeline[(size_t)((blockIdx.y * gridDim.x + blockIdx.x) % 16384) * 8 + 7] = id; }
+#endif
 
     if (ch == a.nchunk) {
         const int R = clampi(a.r_len[u], 0, a.Rcap);
         if (R == 0) return;
         residual_chunk(a, u, bq0, nheads, R, lds);
+        TL(5);
         return;
     }
     const int T = clampi(a.q_len[u], 0, a.Tcap);
     const int t_begin = ch * a.chunk;
     const int t_end = min(T, t_begin + a.chunk);
     if (t_begin >= t_end) return;
+    TL(1);
 
     _Float16 *ps = lds + wave * WAVE_HALFS;
 
@@ -582,14 +595,18 @@ __global__ __launch_bounds__(256, 2) void decode_tiled_kernel(DecArgs a)
         auto tp_of = [&](int i) { return t_begin + (wave + 4 * (i < cnt ? i : cnt - 1)) * kPass; };
         KD kd = load_k(tp_of(0));
         VD vd = load_v(tp_of(0));
+        TL(2);
         for (int i = 0; i < cnt; i++) {
             const int tp = tp_of(i);
             k_phase(kd, tp);
+            if (i == 0) TL(3);
             kd = load_k(tp_of(i + 1));
             v_phase(vd, tp);
             vd = load_v(tp_of(i + 1));
+            if (i == 0) TL(4);
         }
     }
+    TL(5);
 
     // ---------------- finish the wave: undo operand scalings, add the zero-point term
     const float vun = 16777216.0f / 16.0f;                 // 2^24 (subnormal fields) / 2^4 (ps headroom)
@@ -644,7 +661,15 @@ __global__ __launch_bounds__(256, 2) void decode_tiled_kernel(DecArgs a)
         pp[4 + c] = O;
         if (c == 0) { pp[0] = M; pp[1] = L; }
     }
+    TL(6);
 }
+
+#ifdef MINIKV_TIMELINE
+extern "C" int minikv_debug_timeline(long long *host, int n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_timeline), (size_t)n * 8, 0, hipMemcpyDeviceToHost);
+}
+#endif
 
 template <int G, bool LO>
 static int launch_tiled(const DecArgs &a, int units, hipStream_t st)
