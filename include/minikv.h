@@ -124,9 +124,10 @@ int kv_flush_residual(const minikv_shape *shape, minikv_cache *cache, void *stre
  * over the q_len[u] quantized and r_len[u] residual tokens of unit u = b*Hkv + hq/(Hq/Hkv), one softmax
  * over the concatenation, fp32 accumulation, fp16 result.  A unit with no tokens gives zeros.
  *   q    fp16 [B][Hq][D]  (device, read)      out  fp16 [B][Hq][D]  (device, written)
- *   workspace  device scratch of at least minikv_workspace_bytes(shape) bytes, 16-byte aligned; its
- *              contents need not be initialised and are undefined afterwards.  Two calls that share a
- *              workspace must be ordered (same stream). */
+ *   workspace  device scratch of at least minikv_workspace_bytes(shape) bytes, 16-byte aligned.  It must
+ *              be ZERO-FILLED ONCE after allocation (it starts with per-unit ticket counters that every
+ *              call returns to zero); beyond that its contents are private to the library.  Two calls
+ *              that share a workspace must be ordered (same stream). */
 int minikv_decode_attn(const minikv_shape *shape, const minikv_f16 *q, const minikv_cache *cache,
                        float sm_scale, minikv_f16 *out, void *workspace, size_t workspace_bytes,
                        void *stream);

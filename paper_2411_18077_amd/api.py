@@ -107,7 +107,7 @@ class Cache:
             dt = _BUF_DTYPE[name]
             n = max(nbytes // dt.itemsize, 1)         # Rcap == 0: a 1-element placeholder
             self.t[name] = torch.zeros(n, dtype=dt, device=device)
-        self.workspace = torch.empty(max(workspace_bytes(shape), 16), dtype=torch.uint8, device=device)
+        self.workspace = torch.zeros(max(workspace_bytes(shape), 16), dtype=torch.uint8, device=device)   # zeroed once
 
     def __getattr__(self, name):
         t = self.__dict__.get("t", {})

@@ -90,9 +90,13 @@ size_t minikv_buffer_bytes(const minikv_shape *s, int which)
 size_t minikv_workspace_bytes(const minikv_shape *s)
 {
     if (validate_shape(s) != MINIKV_OK) return 0;
-    // sized for the smallest chunk any variant uses, plus the residual chunk
+    // cross-check kernel: one partial per (query row, chunk) for the smallest chunk, plus the residual chunk
     const size_t nch = (size_t)(s->Tcap + kMinChunk - 1) / kMinChunk + 1;
-    return (size_t)s->B * s->Hq * nch * kPartialStride * sizeof(float);
+    const size_t scalar = (size_t)s->B * s->Hq * nch * kPartialStride * sizeof(float);
+    // single-launch kernel: one slot of 4 heads per segment; segments <= waves + 2 * (units x head sets)
+    const size_t nu = (size_t)s->B * s->Hkv * ((s->Hq / s->Hkv + 3) / 4);
+    const size_t stream = ((size_t)kMaxStreamWaves + 2 * nu) * 4 * kPartialStride * sizeof(float);
+    return ws_counter_bytes(*s) + (scalar > stream ? scalar : stream);
 }
 
 int kv_quantize_pack(const minikv_shape *s, const minikv_f16 *K, const minikv_f16 *V, int64_t L,
@@ -140,7 +144,7 @@ int minikv_decode_attn(const minikv_shape *s, const minikv_f16 *q, const minikv_
     if (!aligned16(q) || !aligned16(out) || !aligned16(workspace)) return MINIKV_EINVAL;
     if (!(sm_scale == sm_scale) || sm_scale - sm_scale != 0.0f) return MINIKV_EINVAL;   // NaN / Inf
     if (workspace_bytes < minikv_workspace_bytes(s)) return MINIKV_EWORKSPACE;
-    return launch_decode(*s, q, *c, sm_scale, out, (float *)workspace, g_variant.load(), (hipStream_t)stream);
+    return launch_decode(*s, q, *c, sm_scale, out, workspace, g_variant.load(), (hipStream_t)stream);
 }
 
 int minikv_set_variant(int variant)

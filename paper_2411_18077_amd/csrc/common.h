@@ -14,6 +14,14 @@ constexpr int kVTile = 64;         // tokens per V code tile (4*D words)
 constexpr int kPartialStride = 132;  // floats per split-K partial: m, l, 2 pad, o[128]
 constexpr int kMinChunk = 512;     // smallest token chunk one workgroup of the decode kernel takes
 constexpr int kMaxRep = 8;         // most query heads per KV head
+constexpr int kMaxStreamWaves = 4096;  // most single-wave workgroups the decode kernel is launched with
+
+// Workspace layout: ticket counters first (one int per (unit, set of 4 query heads)), then the partials.
+__host__ __device__ inline size_t ws_counter_bytes(const minikv_shape &s)
+{
+    const size_t n = (size_t)s.B * s.Hkv * ((s.Hq / s.Hkv + 3) / 4);
+    return (n * sizeof(int) + 255) / 256 * 256;
+}
 
 // per-unit element counts
 __host__ __device__ inline size_t kc_words(int Tcap) { return (size_t)Tcap / kKTile * 1024; }
@@ -62,6 +70,6 @@ int launch_quantize(const minikv_shape &s, const minikv_f16 *K, const minikv_f16
 int launch_append(const minikv_shape &s, const minikv_f16 *k_new, const minikv_f16 *v_new,
                   const minikv_cache &c, hipStream_t st);
 int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
-                  minikv_f16 *out, float *ws, int variant, hipStream_t st);
+                  minikv_f16 *out, void *workspace, int variant, hipStream_t st);
 
 }  // namespace minikv

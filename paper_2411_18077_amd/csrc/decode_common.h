@@ -11,10 +11,27 @@ struct DecArgs {
     const uint16_t *Ks, *Kz, *Vs, *Vz, *Rk, *Rv;
     const int32_t *q_len, *r_len;
     uint16_t *out;               // [B][Hq][D] fp16
-    float *ws;                   // split-K partials [B*Hq][nchunk+1][kPartialStride]
+    float *ws;                   // split-K partials (layout depends on the variant)
+    int *cnt;                    // per-unit ticket counters of the single-launch kernel (zero between calls)
     float c1;                    // sm_scale * log2(e): scores are kept in the base-2 domain
     int Hq, Hkv, rep, Tcap, Rcap, chunk, nchunk;
+    int units, hsets;            // B*Hkv; sets of 4 query heads per KV head (1 or 2)
+    int hs_shift;                // log2(hsets)
+    uint32_t hkv_magic, hkv_shift;   // exact division by Hkv: see fast_div()
 };
+
+// n / d for any 32-bit n, with (magic, shift) from fast_div_setup(d) -- no integer divide on the device.
+__host__ __device__ inline uint32_t fast_div(uint32_t n, uint32_t magic, uint32_t shift)
+{
+    const uint32_t hi = (uint32_t)(((uint64_t)n * magic) >> 32);
+    return (uint32_t)(((uint64_t)hi + n) >> shift);
+}
+inline void fast_div_setup(uint32_t d, uint32_t &magic, uint32_t &shift)
+{
+    shift = 0;
+    while ((1ull << shift) < d) shift++;
+    magic = (uint32_t)((((1ull << shift) - d) << 32) / d + 1);
+}
 
 // Partial of (query row bq, chunk ch): [0] running max (base-2 domain), [1] sum of weights,
 // [4..131] un-normalised output.  Chunk index nchunk is the fp16 residual.

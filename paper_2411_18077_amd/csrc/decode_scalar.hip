@@ -189,21 +189,26 @@ int launch_decode_scalar(const DecArgs &a, int G, int units, hipStream_t st)
 }
 
 int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
-                  minikv_f16 *out, float *ws, int variant, hipStream_t st)
+                  minikv_f16 *out, void *workspace, int variant, hipStream_t st)
 {
     const DecodeGeom g = decode_geom(s);
     DecArgs a;
     a.q = q; a.Kc = c.Kc; a.Vc = c.Vc; a.Ks = c.Ks; a.Kz = c.Kz; a.Vs = c.Vs; a.Vz = c.Vz;
     a.Rk = c.Rk; a.Rv = c.Rv; a.q_len = c.q_len; a.r_len = c.r_len;
-    a.out = out; a.ws = ws;
+    a.out = out;
+    a.cnt = reinterpret_cast<int *>(workspace);
+    a.ws = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + ws_counter_bytes(s));
     a.c1 = sm_scale * 1.44269504088896340736f;
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.rep = g.rep; a.Tcap = s.Tcap; a.Rcap = s.Rcap;
     a.chunk = g.chunk; a.nchunk = g.nchunk;
     const int units = s.B * s.Hkv;
+    a.units = units; a.hsets = (g.rep + 3) / 4;
+    a.hs_shift = a.hsets > 1 ? 1 : 0;
+    fast_div_setup((uint32_t)s.Hkv, a.hkv_magic, a.hkv_shift);
     int rc;
     if (variant == 0) variant = 3;                     // default variant
     if (variant == 1) rc = launch_decode_scalar(a, s.G, units, st);
-    else rc = launch_decode_tiled(a, s.G, units, variant, st);
+    else return launch_decode_tiled(a, s.G, units, variant, st);      // merges in the same launch
     if (rc) return rc;
     return launch_merge(a, s.B * s.Hq, st);
 }
