@@ -2,7 +2,6 @@
 #include "common.h"
 
 #include <atomic>
-#include <cstdlib>
 
 namespace minikv {
 
@@ -23,12 +22,11 @@ int validate_shape(const minikv_shape *s)
 
 DecodeGeom decode_geom(const minikv_shape &s)
 {
-    // Chunk size: enough workgroups to cover the chip several times over, but no smaller than kMinChunk
-    // so that the split-K partials stay a small fraction of the bytes read.
+    // Token chunks of the cross-check kernel (the single-launch kernel balances by itself): enough
+    // workgroups to cover the chip several times over, but no smaller than kMinChunk.
     const long units = (long)s.B * s.Hkv;
     int chunk = kMinChunk;
     while (chunk < 4096 && units * ((s.Tcap + 2 * chunk - 1) / (2 * chunk)) >= 2048) chunk *= 2;
-    if (const char *e = getenv("MINIKV_CHUNK")) { int v = atoi(e); if (v >= 512 && v % 512 == 0) chunk = v; }
     DecodeGeom g;
     g.chunk = chunk;
     g.nchunk = (s.Tcap + chunk - 1) / chunk;

@@ -1,4 +1,4 @@
-// Wave-tiled decode attention over the packed 2-bit cache (gfx950, wave64).
+// Decode attention over the packed 2-bit cache: the one-launch kernel of minikv_decode_attn (gfx950, wave64).
 //
 // Computes Algorithm 1 lines 17-19 of the MiniKV paper (scores of the dequantized keys and the fp16
 // residual keys, one softmax, weighted dequantized + residual values; eq. (1) scale passed in) with the
@@ -9,23 +9,27 @@
 //
 // so the inner products run over the raw 2-bit codes and the scales move onto the small operands.
 //
-// Work split: one workgroup (4 waves) per (unit, token chunk); inside it every wave is independent and
-// walks "passes" of 128 tokens with its own online-softmax state; waves merge through LDS at the end and
-// the workgroup writes one split-K partial (merged by merge_kernel).
+// Work split: a flat, weighted list of work items (passes of 128 quantized tokens, items of 64 fp16
+// residual tokens) over all (batch, KV head) units is cut into equal ranges, one per single-wave
+// workgroup; see "Work distribution" below.  Every wave keeps its own online-softmax state and the last
+// wave to finish a unit merges the unit's partial results, all inside one launch.
 //
-// One pass, lane l of the wave:
-//   K phase: the lane owns tokens 2l and 2l+1.  Four 128-bit loads bring their 2 x 8 code words.  The
-//     wave builds, per K group of the pass, a table qs[g][c] = q_c * Ks[g,c] in LDS as an fp16 pair
-//     (hi, lo) whose sum is the exact product, pre-multiplied by 4^-j (see below).  Codes are NOT
-//     converted: (word & (0x00030003 << 2j)) is used directly as two fp16 SUBNORMALS code * 4^j * 2^-24
-//     (j <= 4 keeps the field inside the mantissa; fields 5..7 come from the word shifted right by 6).
-//     The 4-head x 4-channel block products go either to v_mfma_f32_4x4x4f16 (16 blocks = 64 tokens per
-//     instruction, lane = token, 4 result registers = 4 query heads) or to v_dot2_f32_f16.
-//   softmax: per-head wave maximum, lazy rescale of the accumulators, p = exp2(score - m).
-//   V phase: the lane owns channels l and l+64.  ps[gc][h][t] = p * Vs * 2^4 * 4^-j(t) goes to LDS as
-//     fp16; the V words (16 tokens of one channel, even tokens in the low half-word) are masked the same
-//     way and multiplied 4 tokens x 4 heads at a time.  The zero-point term is accumulated per lane in
-//     fp32 and reduced once per chunk.
+// One pass of 128 quantized tokens, lane l of the wave:
+//   K phase: the lane owns tokens 2l and 2l+1; four 128-bit loads bring their 2 x 8 code words.  Codes
+//     are NOT converted: (word & (0x00030003 << 2j)) is used directly as two fp16 SUBNORMALS
+//     code * 4^j * 2^-24 (j <= 4 keeps the field inside the mantissa; fields 5..7 come from the word
+//     shifted right by 6), the 4^-j sits on the other operand and the 2^24 on the result.  The products
+//     go to v_mfma_f32_4x4x4f16: 16 blocks = 64 tokens per instruction, lane = token, the 4 result
+//     registers = 4 query heads, k = 4 channels.  The other operand, q_c * Ks[g,c] for (head, 4 channels),
+//     is an exact fp16 pair (hi, lo) computed in registers by the lanes of the token's K group and handed
+//     to the whole group by the instruction's block broadcast (cbsz / abid), so it never touches LDS;
+//     the K scale / zero rows are stored so that each lane's channel quads are contiguous.
+//   softmax: per-head wave maximum (DPP), lazy rescale of the accumulators, p = exp2(score - m).
+//   V phase: the lane owns channels l and l+64.  ps[gc][h][t] = p * Vs * 2^4 * 4^-j(t) goes through LDS as
+//     fp16 (written by the token lanes, read once by the lanes that supply it, again broadcast by the
+//     instruction); the V words (16 tokens of one channel, even tokens in the low half-word) are masked
+//     like the K words and multiplied 4 tokens x 4 heads at a time.  The zero-point term is accumulated
+//     per lane in fp32 and reduced once per segment.
 //
 // Input domain implied by the fp16 operands: |q * Ks| < 65504 and Vs < 4096 (V group range < 12288).
 #include "decode_common.h"
@@ -47,7 +51,6 @@ constexpr int kKRowH = kD + 8;         // halfs per staged residual key row (272
 
 __device__ inline h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
 __device__ inline uint32_t as_u32(h2 h) { return __builtin_bit_cast(uint32_t, h); }
-__device__ inline float h2f(uint16_t h) { return __half2float(__ushort_as_half(h)); }
 
 // field j (0..7) of a half-word pair -> (shift inside the mantissa, use the >>6 copy?)
 __host__ __device__ constexpr int fld_shift(int j) { return j <= 4 ? 2 * j : 2 * (j - 3); }
@@ -67,48 +70,7 @@ __device__ inline float dpp_mov(float old, float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old), __builtin_bit_cast(int, v),
                                                                   CTRL, ROW_MASK, 0xF, false));
 }
-constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140,
-              kDppBcast15 = 0x142, kDppBcast31 = 0x143;
 
-// maximum over the 64 lanes, returned wave-uniform
-__device__ inline float wave_max64(float v)
-{
-    v = fmaxf(v, dpp_mov<kDppXor1>(v, v));
-    v = fmaxf(v, dpp_mov<kDppXor2>(v, v));
-    v = fmaxf(v, dpp_mov<kDppHalfMirror>(v, v));
-    v = fmaxf(v, dpp_mov<kDppMirror>(v, v));               // every row of 16 lanes now holds its maximum
-    v = fmaxf(v, dpp_mov<kDppBcast15, 0xA>(v, v));         // rows 1 and 3 take in rows 0 and 2
-    v = fmaxf(v, dpp_mov<kDppBcast31, 0xC>(v, v));         // rows 2 and 3 take in lane 31
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
-}
-// sum over aligned groups of N lanes (N = 4, 8 or 16), result in every lane of the group
-template <int N>
-__device__ inline float row_sum(float v)
-{
-    v += dpp_mov<kDppXor1>(v, v);
-    v += dpp_mov<kDppXor2>(v, v);
-    if constexpr (N >= 8) v += dpp_mov<kDppHalfMirror>(v, v);
-    if constexpr (N >= 16) v += dpp_mov<kDppMirror>(v, v);
-    return v;
-}
-// sum over the 64 lanes, returned wave-uniform
-__device__ inline float wave_sum64(float v)
-{
-    v = row_sum<16>(v);
-    v += dpp_mov<kDppBcast15, 0xA>(0.f, v);
-    v += dpp_mov<kDppBcast31, 0xC>(0.f, v);
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
-}
-// sum over aligned groups of N lanes for N up to 64
-template <int N>
-__device__ inline float group_sum(float v)
-{
-    if constexpr (N <= 16) return row_sum<N>(v);
-    v = row_sum<16>(v);
-    v += __shfl_xor(v, 16);
-    if constexpr (N == 64) v += __shfl_xor(v, 32);
-    return v;
-}
 // Four independent reductions at once, hand-scheduled: step k of all four values is issued back to back,
 // so the two wait states a DPP read needs after a VALU write are always covered by the other three.
 #define MINIKV_DPP4(op, ctrl)                                                     \
@@ -142,24 +104,6 @@ __device__ inline void wave_sum64x4(float v[4])
     asm volatile("s_nop 1\n" MINIKV_WAVE64("add") : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
     for (int i = 0; i < 4; i++) v[i] = lane63(v[i]);
 }
-// v[i] <- sum over aligned groups of N lanes, in every lane of the group
-template <int N>
-__device__ inline void group_sum_x4(float v[4])
-{
-    if constexpr (N == 8) {
-        asm volatile("s_nop 1\n" MINIKV_DPP4("add", "quad_perm:[1,0,3,2] row_mask:0xf")
-                     MINIKV_DPP4("add", "quad_perm:[2,3,0,1] row_mask:0xf")
-                     MINIKV_DPP4("add", "row_half_mirror row_mask:0xf")
-                     : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
-    } else {
-        asm volatile("s_nop 1\n" MINIKV_ROW16("add") : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
-        if constexpr (N >= 32)
-            for (int i = 0; i < 4; i++) v[i] += __shfl_xor(v[i], 16);
-        if constexpr (N == 64)
-            for (int i = 0; i < 4; i++) v[i] += __shfl_xor(v[i], 32);
-    }
-}
-
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; exp2(-inf) = 0
 
 template <int N> struct Words { uint32_t v[N]; };

@@ -1,0 +1,73 @@
+"""GPU parity at the full sizes of the five baseline configurations, in the launch configuration that
+bench.py times (default variant, one append + one decode call).  The oracle is evaluated on a seeded
+sample of (batch, KV-head) units -- all of them for the two small configurations, 16 for the others plus
+the shortest and the longest unit of the ragged one -- and the packed cache of the sampled units must
+match the oracle's bit for bit."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2411_18077_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def g():
+    import gpu_common
+    assert torch.cuda.is_available()
+    return gpu_common
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+def test_full_config_sampled_units(g, name):
+    from oracle import ref
+    from paper_2411_18077_amd import api
+    w = W.by_name(name)
+    inp = W.make_inputs(w, "cuda")
+    shape = api.make_shape(w.B, w.Hq, w.Hkv, w.D, w.G, inp.Tcap, w.Rcap)
+    cache = api.Cache(shape)
+    api.kv_quantize_pack(shape, inp.K, inp.V, w.L, inp.idx, inp.idx.shape[1], inp.n_tok, int(inp.n_tok.max()), cache)
+    r0 = w.Rcap - 1
+    cache.Rk.view(w.units, w.Rcap, w.D)[:, :r0].copy_(inp.Rk[:, :r0])
+    cache.Rv.view(w.units, w.Rcap, w.D)[:, :r0].copy_(inp.Rv[:, :r0])
+    cache.r_len.fill_(r0)
+    api.kv_append_residual(shape, inp.Rk[:, r0].contiguous(), inp.Rv[:, r0].contiguous(), cache)
+    out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=torch.float16, device="cuda")
+    api.minikv_decode_attn(shape, inp.q, cache, 1.0 / math.sqrt(w.D), out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+
+    n_tok = inp.n_tok.cpu().numpy()
+    if w.units <= 256:
+        units = list(range(w.units))
+    else:
+        rng = np.random.default_rng(w.seed)
+        units = sorted(set(rng.choice(w.units, 16, replace=False).tolist()))
+    if w.keep is None:
+        units = sorted(set(units) | {int(np.argmin(n_tok)), int(np.argmax(n_tok))})
+    rep = w.Hq // w.Hkv
+    rs = ref.RefShape(len(units), rep, 1, w.D, w.G, inp.Tcap, w.Rcap)
+    rc = g.ref_build_cache(inp, rs, r_len=w.Rcap, units=units)
+    g.assert_cache_bit_exact(cache, rc, unit_map=units)
+    sel = torch.as_tensor(units, device="cuda")
+    q = inp.q.view(w.B, w.Hkv, rep, w.D).reshape(w.units, rep, w.D)[sel].cpu().numpy()
+    want, want64, _ = ref.decode_attn(rc, q, 1.0 / math.sqrt(w.D), want_f64=True)
+    got = out.view(w.B, w.Hkv, rep, w.D).reshape(w.units, rep, w.D)[sel].float().cpu().numpy().astype(np.float64)
+    # The bar is 2e-3 absolute.  Above |o| = 2 the spacing of fp16 itself exceeds that (2^-9 in [2, 4),
+    # 2^-8 in [4, 8), ...), so two correctly rounded results of nearly equal sums may sit one fp16 step
+    # apart; there the bar is one step of the oracle's value (heavy-tailed data reach such magnitudes).
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want64), 2.0 ** -14))) - 10)
+    tol = np.maximum(TOL, ulp)
+    diff = np.abs(got - want.astype(np.float64))
+    assert np.all(diff <= tol), "max-abs error %g (|o| up to %g) on %s" % (diff.max(), np.abs(want64).max(), name)
+    # where the step exceeds the bar, the GPU value must still be (nearly) a correct rounding of the fp64 result
+    big = np.abs(want64) >= 2.0
+    pre = (np.abs(got - want64) / ulp)[big]
+    worst = float(pre.max()) if pre.size else 0.0
+    assert worst <= 0.75, "%.3f fp16 steps from the fp64 result on %s" % (worst, name)
+    print("%s: max |diff| %.3g, max |o| %.3g, %d outputs above 2, worst distance there %.3f steps"
+          % (name, diff.max(), np.abs(want64).max(), int(big.sum()), worst))
