@@ -26,6 +26,14 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes one launch of the decode kernel moves, from hardware counters (rocprofv3 --pmc FETCH_SIZE and
+# --pmc WRITE_SIZE runs of this script, each reading scaled by what the same counter shows for the plain
+# 1 GiB device copies of --calibrate-copy); the summaries are kept under profiles/.  Counter runs cannot
+# be made from inside a timed run, so the figure is recorded here per workload; None = not measured.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg4_llama3_8b_gqa_32k": 186620723,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -162,7 +170,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u2 codes, fp16 operands, fp32 accumulate",
+        "dtype": "f16",
         "data": "synthetic",
         "config": {
             "workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "context": w.L,
@@ -170,12 +178,14 @@ def main():
             "G": w.G, "residual": w.Rcap, "Tcap": int(shape.Tcap), "cache_copies": ncopy,
             "algorithmic_bytes_per_step": alg_bytes, "variant": args.variant,
             "step": "kv_append_residual + minikv_decode_attn",
+            "arithmetic": "2-bit codes as fp16 operands, fp32 accumulation, fp16 result",
         },
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 1),
         "roofline": {
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-            "kernel": "minikv_decode_attn (tile kernel + split-K merge)",
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+            "kernel": "decode_stream_kernel (the single launch of minikv_decode_attn)",
+            "algorithmic_bytes_per_launch": alg_bytes,
             "avg_launch_us": round(attn_ms_avg * 1e3, 2), "median_launch_us": round(attn_ms_med * 1e3, 2),
         },
     }
