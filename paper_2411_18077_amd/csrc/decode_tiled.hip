@@ -9,10 +9,11 @@
 //
 // so the inner products run over the raw 2-bit codes and the scales move onto the small operands.
 //
-// Work split: a flat, weighted list of work items (passes of 128 quantized tokens, items of 64 fp16
-// residual tokens) over all (batch, KV head) units is cut into equal ranges, one per single-wave
-// workgroup; see "Work distribution" below.  Every wave keeps its own online-softmax state and the last
-// wave to finish a unit merges the unit's partial results, all inside one launch.
+// Work split: single-wave workgroups, as many as the chip holds.  A flat, weighted list of work items
+// (items of 64 fp16 residual tokens, passes of 128 quantized tokens) over all (batch, KV head) units is cut
+// into equal ranges, one per wave; see "Work distribution" below.  Every wave keeps one online-softmax
+// state per unit it touches and the last wave to finish a unit merges the unit's partial results, all
+// inside one launch.
 //
 // One pass of 128 quantized tokens, lane l of the wave:
 //   K phase: the lane owns tokens 2l and 2l+1; four 128-bit loads bring their 2 x 8 code words.  Codes
@@ -29,167 +30,31 @@
 //     fp16 (written by the token lanes, read once by the lanes that supply it, again broadcast by the
 //     instruction); the V words (16 tokens of one channel, even tokens in the low half-word) are masked
 //     like the K words and multiplied 4 tokens x 4 heads at a time.  The zero-point term is accumulated
-//     per lane in fp32 and reduced once per segment.
+//     per lane in fp32 and reduced once per unit and wave.
 //
 // Input domain implied by the fp16 operands: |q * Ks| < 65504 and Vs < 4096 (V group range < 12288).
-#include "decode_common.h"
-
-#include <hip/hip_fp16.h>
+#include "decode_wave.h"
 
 namespace minikv {
 
-typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-typedef float f4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-
-constexpr int kNH = 4;                 // query-head slots per workgroup (rows of the 4x4x4 blocks)
-constexpr int kPass = 128;             // tokens per wave pass
-constexpr int kPsH = kPass + 4;        // halfs per (channel group, head) row of ps, padded
-constexpr int kPsG = kNH * kPsH;       // halfs per channel group of ps (528: shifts 8 banks)
-constexpr int kKRowH = kD + 8;         // halfs per staged residual key row (272 B: rows start 4 banks apart)
-
-__device__ inline h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
-__device__ inline uint32_t as_u32(h2 h) { return __builtin_bit_cast(uint32_t, h); }
-
-// field j (0..7) of a half-word pair -> (shift inside the mantissa, use the >>6 copy?)
-__host__ __device__ constexpr int fld_shift(int j) { return j <= 4 ? 2 * j : 2 * (j - 3); }
-__host__ __device__ constexpr bool fld_shifted(int j) { return j > 4; }
-// 4^-(shift/2): what the small operand is pre-multiplied by so that the masked subnormal needs no shift
-__device__ inline float fld_scale(int j) { return 1.0f / (float)(1 << fld_shift(j)); }
-
-__device__ inline h2 field(uint32_t w, uint32_t w6, int j)
-{
-    return as_h2((fld_shifted(j) ? w6 : w) & (0x00030003u << fld_shift(j)));
-}
-
-// ---- cross-lane reductions on the DPP data path (no LDS traffic)
-template <int CTRL, int ROW_MASK = 0xF>
-__device__ inline float dpp_mov(float old, float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old), __builtin_bit_cast(int, v),
-                                                                  CTRL, ROW_MASK, 0xF, false));
-}
-
-// Four independent reductions at once, hand-scheduled: step k of all four values is issued back to back,
-// so the two wait states a DPP read needs after a VALU write are always covered by the other three.
-#define MINIKV_DPP4(op, ctrl)                                                     \
-    "v_" op "_f32_dpp %0, %0, %0 " ctrl " bank_mask:0xf\n"                        \
-    "v_" op "_f32_dpp %1, %1, %1 " ctrl " bank_mask:0xf\n"                        \
-    "v_" op "_f32_dpp %2, %2, %2 " ctrl " bank_mask:0xf\n"                        \
-    "v_" op "_f32_dpp %3, %3, %3 " ctrl " bank_mask:0xf\n"
-#define MINIKV_ROW16(op)                                                          \
-    MINIKV_DPP4(op, "quad_perm:[1,0,3,2] row_mask:0xf")                           \
-    MINIKV_DPP4(op, "quad_perm:[2,3,0,1] row_mask:0xf")                           \
-    MINIKV_DPP4(op, "row_half_mirror row_mask:0xf")                               \
-    MINIKV_DPP4(op, "row_mirror row_mask:0xf")
-#define MINIKV_WAVE64(op)                                                         \
-    MINIKV_ROW16(op)                                                              \
-    MINIKV_DPP4(op, "row_bcast:15 row_mask:0xa")                                  \
-    MINIKV_DPP4(op, "row_bcast:31 row_mask:0xc")
-
-__device__ inline float lane63(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
-}
-// v[i] <- maximum of v[i] over the wave (wave-uniform)
-__device__ inline void wave_max64x4(float v[4])
-{
-    asm volatile("s_nop 1\n" MINIKV_WAVE64("max") : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
-    for (int i = 0; i < 4; i++) v[i] = lane63(v[i]);
-}
-// v[i] <- sum of v[i] over the wave (wave-uniform)
-__device__ inline void wave_sum64x4(float v[4])
-{
-    asm volatile("s_nop 1\n" MINIKV_WAVE64("add") : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
-    for (int i = 0; i < 4; i++) v[i] = lane63(v[i]);
-}
-__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32; exp2(-inf) = 0
-
-template <int N> struct Words { uint32_t v[N]; };
-template <int N> __device__ inline Words<N> load_words(const void *p)
-{
-    Words<N> r;
-    if constexpr (N == 1) { r.v[0] = *reinterpret_cast<const uint32_t *>(p); }
-    else if constexpr (N == 2) { uint2 t = *reinterpret_cast<const uint2 *>(p); r.v[0] = t.x; r.v[1] = t.y; }
-    else {
-        for (int i = 0; i < N / 4; i++) {
-            uint4 t = reinterpret_cast<const uint4 *>(p)[i];
-            r.v[4 * i] = t.x; r.v[4 * i + 1] = t.y; r.v[4 * i + 2] = t.z; r.v[4 * i + 3] = t.w;
-        }
-    }
-    return r;
-}
-
-// The broadcast controls of the matrix instruction are immediates; these helpers turn the (unrolled,
-// hence constant) block index into one.
-#define MINIKV_MFMA_CASE(n) case n: acc = __builtin_amdgcn_mfma_f32_4x4x4f16(av, bv, acc, CB, n, 0); break;
-template <int CB>
-__device__ inline void mfma_bc(f4 &acc, h4 av, h4 bv, int abid)
-{
-    switch (abid) {
-        MINIKV_MFMA_CASE(0) MINIKV_MFMA_CASE(1) MINIKV_MFMA_CASE(2) MINIKV_MFMA_CASE(3)
-        MINIKV_MFMA_CASE(4) MINIKV_MFMA_CASE(5) MINIKV_MFMA_CASE(6) MINIKV_MFMA_CASE(7)
-        MINIKV_MFMA_CASE(8) MINIKV_MFMA_CASE(9) MINIKV_MFMA_CASE(10) MINIKV_MFMA_CASE(11)
-        MINIKV_MFMA_CASE(12) MINIKV_MFMA_CASE(13) MINIKV_MFMA_CASE(14) MINIKV_MFMA_CASE(15)
-    }
-}
-template <int CB>
-__device__ inline void mfma_k(f4 &acc0, f4 &acc1, h4 av, h4 b0, h4 b1, int abid)
-{
-    mfma_bc<CB>(acc0, av, b0, abid);
-    mfma_bc<CB>(acc1, av, b1, abid);
-}
-template <int CB>
-__device__ inline void mfma_v(f4 &o0, f4 &o1, h4 a0, h4 a1, h4 b0, h4 b1, int abid)
-{
-    mfma_bc<CB>(o0, a0, b0, abid);
-    mfma_bc<CB>(o1, a1, b1, abid);
-}
-
 // ------------------------------------------------------------------------------------------------
-constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
-
-template <int N>
-__device__ inline float dpp_ror_add(float v)              // v + (v rotated right by N lanes inside its row of 16)
-{
-    return v + dpp_mov<0x120 + N>(0.f, v);
-}
-template <int H>
-__device__ inline float quad_bcast(float v)               // value of lane (4*(lane/4) + H)
-{
-    return dpp_mov<H * 0x55>(0.f, v);
-}
-
-// What one wave needs from global memory for the K half and the V half of one pass of 128 tokens.
-template <int NKW>
-struct KData {
-    u4 kw[4];               // K code words of tokens 2*lane (kw[0..1]) and 2*lane+1 (kw[2..3])
-    Words<NKW> ks, kz;      // this lane's bin of the K scale / zero row of its group
-};
-template <int NCG>
-struct VData {
-    u4 vw[2][2];            // V code words [channel lane / lane+64][64-token tile]: 4 blocks of 16 tokens each
-    Words<NCG> vs, vz;      // V scale / zero of tokens 2*lane and 2*lane+1 (zero when past the end)
-};
-
-// ------------------------------------------------------------------------------------------------
-// Work distribution ("flat list"): every unit (batch, KV head, set of 4 query heads) contributes
-// ceil(T/128) quantized passes followed by ceil(R/64) residual items; the concatenation of all units'
-// items is cut into gridDim.x equal ranges, one per single-wave workgroup.  A maximal run of items of one
-// kind inside one unit and one wave is a "segment": it ends with one split-K partial (running max, sum,
-// un-normalised output).  The segment that arrives last at its unit (device-scope ticket counter) merges
-// the unit's partials and writes the fp16 output, so one kernel launch does the whole call and ragged
-// lengths are balanced by construction.
-struct UnitItems { int nq, nr; };
-constexpr int kWQ = 2, kWR = 7;        // relative cost of a quantized pass (128 tokens, 12 KB) and a residual
+// Work distribution.  Every unit (batch, KV head, set of 4 query heads) has ceil(R/64) residual items
+// followed by ceil(T/128) quantized passes.  The units' weights (kWR per residual item, kWQ per pass) are
+// laid end to end and the line is cut into NW equal ranges, one per wave; a wave owns the items that
+// START inside its range, so ragged lengths are balanced by construction.  What a wave does for one unit
+// ends in one split-K partial (running max, sum, un-normalised output); the partial that arrives last at
+// its unit (device-scope ticket counter) merges the unit's partials and writes the fp16 output, so one
+// kernel launch does the whole call.  (Drawing passes from a per-unit counter instead was tried: a vector
+// atomic per pass, even one whose result is needed a full pass later, slowed the pass loop by 40 %.)
+struct UnitItems { int nq, nr, T, R; };
+constexpr int kWQ = 2, kWR = 5;        // relative cost of a quantized pass (128 tokens, 12 KB) and a residual
                                        // item (64 fp16 tokens, 32 KB), measured
 
 __device__ inline UnitItems unit_items(const DecArgs &a, int up)
 {
     const int u = up >> a.hs_shift;
     const int T = clampi(a.q_len[u], 0, a.Tcap), R = clampi(a.r_len[u], 0, a.Rcap);
-    return UnitItems{(T + kPass - 1) / kPass, (R + 63) / 64};
+    return UnitItems{(T + kPass - 1) / kPass, (R + 63) / 64, T, R};
 }
 // P weight units are cut into NW = 2^nw_log ranges [w*P >> nw_log, (w+1)*P >> nw_log).
 __device__ inline long range_start(int w, int P, int nw_log) { return ((long)w * P) >> nw_log; }
@@ -217,39 +82,27 @@ __device__ inline int wave_scan_i32(int v)
     return v;
 }
 __device__ inline int wave_sum_i32(int v) { return __builtin_amdgcn_readlane(wave_scan_i32(v), 63); }
-// Split-K partials travel between workgroups (possibly on different XCDs, each with its own L2) inside
-// one launch.  They are written and read with device-scope relaxed atomics, which the hardware performs
-// at the device-coherent level instead of in the XCD-local L2, so no L2 write-back or invalidate is needed;
-// the writer only has to wait for its stores to be acknowledged before it takes the ticket.
-__device__ inline float ld_agent(const float *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline float2 ld_agent2(const float *p)      // two consecutive floats, p 8-byte aligned
-{
-    const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
-    return float2{__builtin_bit_cast(float, (uint32_t)v), __builtin_bit_cast(float, (uint32_t)(v >> 32))};
-}
-__device__ inline void st_agent(float *p, float v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // Split-K partial of (slot, head): [0] running max (base-2 domain), [1] sum of weights, [4..131] output.
 __device__ inline float *slot_ptr(const DecArgs &a, int slot, int h)
 {
     return a.ws + ((size_t)slot * kNH + h) * kPartialStride;
 }
 
+// Optional per-wave cycle accounting for tuning (compiled in only with -DMINIKV_TIMELINE).
 #ifdef MINIKV_TIMELINE
-__device__ long long g_timeline[16384 * 8];
-#define TL(slot) do { if (threadIdx.x == 0) g_timeline[(size_t)(blockIdx.x % 16384) * 8 + (slot)] = __builtin_readcyclecounter(); } while (0)
-__device__ long long g_tl2[16384 * 16];
-#define TL2(slot) do { if (threadIdx.x == 0) g_tl2[(size_t)(blockIdx.x % 16384) * 16 + (slot)] = __builtin_readcyclecounter(); } while (0)
+__device__ long long g_qtl[16384 * 24];
+#define QT_NOW() __builtin_readcyclecounter()
+#define QT_SET(slot, v) do { if (threadIdx.x == 0) g_qtl[(size_t)(blockIdx.x % 16384) * 24 + (slot)] = (v); } while (0)
+#define QT_ADD(slot, v) do { if (threadIdx.x == 0) g_qtl[(size_t)(blockIdx.x % 16384) * 24 + (slot)] += (v); } while (0)
+#define QT_MARK(var) const long long var = QT_NOW()
+extern "C" int minikv_debug_qtl(long long *host, int n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_qtl), (size_t)n * 8, 0, hipMemcpyDeviceToHost);
+}
 #else
-#define TL(slot) do {} while (0)
-#define TL2(slot) do {} while (0)
+#define QT_SET(slot, v) do {} while (0)
+#define QT_ADD(slot, v) do {} while (0)
+#define QT_MARK(var) do {} while (0)
 #endif
 
 template <int G, bool LO>
@@ -267,11 +120,16 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
     typedef VData<NCG> VD;
 
     extern __shared__ __attribute__((aligned(16))) _Float16 lds[];
-    _Float16 *ps = lds;                                    // [NCG][kNH][kPsH] halfs (quantized segments)
+    _Float16 *ps = lds;                                    // [NCG][kNH][kPsH] halfs (quantized passes)
 
-    const int lane = threadIdx.x, w = blockIdx.x;
+    const int lane = threadIdx.x;
     const int NU = a.units * a.hsets;
-    TL(0);
+#ifdef MINIKV_TIMELINE
+    for (int i = 2; i < 24; i++) QT_SET(i, 0);
+    QT_SET(0, __builtin_amdgcn_s_memrealtime());
+    { unsigned hwid, xcc; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid)); asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc)); QT_SET(13, (long long)hwid | ((long long)xcc << 32)); }
+#endif
+    QT_MARK(t_begin);
 
     // ---------------- total weight of all items; units without any token get their zeros here
     auto unit_weight = [&](int uu) -> int {
@@ -288,7 +146,7 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
         for (int k = 0; k < 4; k++) {
             const int uu = base + 64 * k + lane;
             mine += n[k];
-            if (uu < NU && n[k] == 0 && uu % (int)gridDim.x == w) {
+            if (uu < NU && n[k] == 0 && uu % (int)gridDim.x == (int)blockIdx.x) {
                 const int u = uu >> a.hs_shift, hs = uu & (a.hsets - 1);
                 const int bi = (int)fast_div((uint32_t)u, a.hkv_magic, a.hkv_shift);
                 const int bq0 = bi * a.Hq + (u - bi * a.Hkv) * a.rep + hs * kNH;
@@ -298,12 +156,12 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
         }
     }
     const int P = wave_sum_i32(mine);
-    // The weight line is cut into NW ranges, each at least one residual item long, so that every wave
-    // between the first and the last wave of a unit's passes (or residual items) owns one of them.
-    // NW is a power of two so that the cuts need no division.
+    // The weight line is cut into NW ranges, each at least one residual item long.  NW is a power of two
+    // so that the cuts need no division.
     if (P == 0) return;
     const int nw_cap = max(1, min((int)gridDim.x, P / kWR));
     const int nw_log = 31 - __builtin_clz(nw_cap), NW = 1 << nw_log;
+    const int w = blockIdx.x;
     if (w >= NW) return;
     const long start = range_start(w, P, nw_log), end = range_start(w + 1, P, nw_log);
     const float inv_p = 1.0f / (float)P;
@@ -327,7 +185,8 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
             running += __builtin_amdgcn_readlane(incl, 63);
         }
     }
-    TL(1);
+    QT_MARK(t_prol);
+    QT_ADD(2, t_prol - t_begin);
 
     const int blk4 = lane >> 2, row = lane & 3;            // block of 4 lanes; row = query head this lane
                                                            // supplies as A operand
@@ -338,7 +197,7 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
     const int cg1 = (lane + 64) / G;
     // Tokens 2*lane, 2*lane+1 are field j = lane & 7 of their V word.  The weights of this lane carry the
     // constant factor 2^lg = 16 * 4^-shift so that the masked V field needs no shift; the lane's running
-    // sums l and oz carry the same factor and are unscaled once per segment.
+    // sums l and oz carry the same factor and are unscaled once per unit.
     const float lg = 4.0f - (float)fld_shift(lane & 7);
     const float unlg = fast_exp2(-lg);
     const float kscale = a.c1 * 16777216.0f;               // undo the 2^-24 of the subnormal code fields
@@ -346,99 +205,229 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
 
     // A wave owns the items whose start position lies in [start, end).
     for (; up < NU && ib < end; up++) {
-        TL2(8);
+        QT_MARK(t_u0);
         const UnitItems it = unit_items(a, up);
-        const int wt = kWQ * it.nq + kWR * it.nr;
+        const int wt = kWR * it.nr + kWQ * it.nq;
         if (wt == 0) continue;
-        const long rb = ib + (long)kWQ * it.nq;            // position of the unit's first residual item
-        // (the offsets are clamped to the unit's span first, so 32-bit arithmetic suffices)
+        const long ib_next = ib + wt;
+        // this wave's items of the unit (the offsets are clamped to the unit's span first, so 32-bit
+        // arithmetic suffices): residual items r0..r1-1, passes j0..j1-1
         const int span = wt + kWR;
         const int ds = (int)min((long)span, max(0L, start - ib)), de = (int)min((long)span, max(0L, end - ib));
-        const int j0 = min(it.nq, (ds + kWQ - 1) / kWQ), j1 = min(it.nq, (de + kWQ - 1) / kWQ);
-        const int dq = kWQ * it.nq;
-        const int r0 = min(it.nr, (max(0, ds - dq) + kWR - 1) / kWR), r1 = min(it.nr, (max(0, de - dq) + kWR - 1) / kWR);
+        const int dq = kWR * it.nr;
+        const int r0 = min(it.nr, (ds + kWR - 1) / kWR), r1 = min(it.nr, (de + kWR - 1) / kWR);
+        const int j0 = min(it.nq, (max(0, ds - dq) + kWQ - 1) / kWQ), j1 = min(it.nq, (max(0, de - dq) + kWQ - 1) / kWQ);
+        if (r0 >= r1 && j0 >= j1) { ib = ib_next; continue; }
+        // the waves that own items of this unit: from the owner of the first item to the owner of the last
+        const int wf = wave_of(ib, P, nw_log, inv_p);
+        const int wl = wave_of(ib_next - (it.nq ? kWQ : kWR), P, nw_log, inv_p);
+        const int expected = wl - wf + 1;
         const int u = up >> a.hs_shift, hs = up & (a.hsets - 1);
         const int bi = (int)fast_div((uint32_t)u, a.hkv_magic, a.hkv_shift);
         const int bq0 = bi * a.Hq + (u - bi * a.Hkv) * a.rep + hs * kNH;
         const int nheads = min(kNH, a.rep - hs * kNH);
-        // segments of this unit: waves first..last of its quantized items and of its residual items
-        const int wq0 = it.nq ? wave_of(ib, P, nw_log, inv_p) : 0, wq1 = it.nq ? wave_of(rb - kWQ, P, nw_log, inv_p) : -1;
-        const int wr0 = it.nr ? wave_of(rb, P, nw_log, inv_p) : 0, wr1 = it.nr ? wave_of(ib + wt - kWR, P, nw_log, inv_p) : -1;
-        const int expected = (wq1 - wq0 + 1) + (wr1 - wr0 + 1);
-        const long ib_next = ib + wt;
+        const int t_end = it.T;
+        const uint32_t *Kc = a.Kc + (size_t)u * kc_words(a.Tcap);
+        const uint32_t *Vc = a.Vc + (size_t)u * vc_words(a.Tcap);
+        const uint16_t *Ks = a.Ks + (size_t)u * (a.Tcap / G) * kD;
+        const uint16_t *Kz = a.Kz + (size_t)u * (a.Tcap / G) * kD;
+        const uint16_t *Vs = a.Vs + (size_t)u * a.Tcap * NCG;
+        const uint16_t *Vz = a.Vz + (size_t)u * a.Tcap * NCG;
 
-      TL2(9);
-      for (int kind = 0; kind < 2; kind++) {
-        if (kind == 0 ? j0 >= j1 : r0 >= r1) continue;
+        auto load_k = [&](int tp) -> KD {
+            KD d;
+            const u4 *ktile = reinterpret_cast<const u4 *>(Kc + (size_t)(tp >> 7) * 1024);
+#pragma unroll
+            for (int i = 0; i < 4; i++) d.kw[i] = ktile[i * 64 + lane];
+            const bool gvalid = tp + gl * G < t_end;
+            const size_t go = ((size_t)(tp / G) + (gvalid ? gl : 0)) * kD + bbk * (NKR * 4);
+            d.ks = load_words<NKW>(Ks + go);
+            d.kz = load_words<NKW>(Kz + go);
+            return d;
+        };
+        auto load_v = [&](int tp) -> VD {
+            VD d;
+            const u4 *vtile = reinterpret_cast<const u4 *>(Vc + (size_t)(tp >> 6) * (4 * kD));
+#pragma unroll
+            for (int tl = 0; tl < 2; tl++) {
+                d.vw[0][tl] = vtile[tl * kD + lane];
+                d.vw[1][tl] = vtile[tl * kD + lane + 64];
+            }
+            // past the end the (clamped) load still happens and the value is masked to zero afterwards,
+            // so that the number of loads in flight is the same on every path
+            const bool valid = tp + 2 * lane < t_end;
+            const size_t vo = (size_t)(valid ? tp + 2 * lane : tp) * NCG;
+            d.vs = load_words<NCG>(Vs + vo);
+            d.vz = load_words<NCG>(Vz + vo);
+            return d;
+        };
 
-        float m[kNH], lsum[kNH];                           // result of the segment (wave-uniform m, lsum)
-        float oa[kNH], ob[kNH];                            // un-normalised output of two channels per lane
-        int ca, cb;                                        // which two channels
+        // The tiles of the first pass are requested before anything else is waited for.
+        KD kd = {};
+        VD vd = {};
+        if (j0 < j1) {
+            kd = load_k(j0 * kPass);
+            vd = load_v(j0 * kPass);
+        }
+        // the wave's online-softmax state for this unit
+        float m[kNH], l_lane[kNH];
+        f4 O0 = {0.f, 0.f, 0.f, 0.f}, O1 = {0.f, 0.f, 0.f, 0.f};   // channel lane / lane+64, 4 heads each
+        float oz[kNH][NCG];
+#pragma unroll
+        for (int h = 0; h < kNH; h++) {
+            m[h] = -1e30f; l_lane[h] = 0.f;
+#pragma unroll
+            for (int g = 0; g < NCG; g++) oz[h][g] = 0.f;
+        }
+        QT_MARK(t_u1);
+        QT_ADD(3, t_u1 - t_u0);
 
-        if (kind == 0) {
-            // =============================== quantized passes j0 .. j1-1 of unit u
-            const int j = j0;
-            const int T = clampi(a.q_len[u], 0, a.Tcap);
-            const int t_end = T;
-            const uint32_t *Kc = a.Kc + (size_t)u * kc_words(a.Tcap);
-            const uint32_t *Vc = a.Vc + (size_t)u * vc_words(a.Tcap);
-            const uint16_t *Ks = a.Ks + (size_t)u * (a.Tcap / G) * kD;
-            const uint16_t *Kz = a.Kz + (size_t)u * (a.Tcap / G) * kD;
-            const uint16_t *Vs = a.Vs + (size_t)u * a.Tcap * NCG;
-            const uint16_t *Vz = a.Vz + (size_t)u * a.Tcap * NCG;
+        // =============================== residual items (64 fp16 tokens each): Algorithm 1's R_K t_Q^T and
+        // A_unquant R_V, on the same 4x4x4 matrix instruction as the quantized passes (the vector ALU is
+        // several times slower here because the wave shares its SIMD with one that saturates the matrix
+        // pipe).  The 64 key rows, then the 64 value rows, are fetched with fully coalesced loads (4 rows
+        // per instruction, 16 lanes x 16 B per row) and staged in LDS.  Scores: lane = token, its key row
+        // read back as the B operand, q as the A operand broadcast to all 16 blocks.  Values: lane =
+        // channels lane, lane+64, the B operand gathered token by token from the staged rows, the weights
+        // p (fp16, through LDS) as the broadcast A operand.  The result is folded into the wave's state.
+#pragma unroll 1
+        for (int ri = r0; ri < r1; ri++) {
+            const int R = it.R;
+            _Float16 *pr = lds;                            // [kNH][64 + 8] halfs: weights of the item's tokens
+            _Float16 *rows = lds + kNH * kD;               // [64][kKRowH] halfs: key rows, then value rows
+            constexpr int kPrH = 72;
+            const uint16_t *Rk = a.Rk + (size_t)u * a.Rcap * kD;
+            const uint16_t *Rv = a.Rv + (size_t)u * a.Rcap * kD;
+            const int rsub = lane >> 4, piece = lane & 15;  // row within a group of 4, 16-byte piece of the row
+            const int t0 = ri * 64;
+            const bool valid = t0 + lane < R;
 
+            QT_MARK(t_r0);
+            Words<64> g;
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const int rr = t0 + 4 * i + rsub;
+                const uint4 x = reinterpret_cast<const uint4 *>(Rk + (size_t)(rr < R ? rr : 0) * kD)[piece];
+                g.v[4 * i] = x.x; g.v[4 * i + 1] = x.y; g.v[4 * i + 2] = x.z; g.v[4 * i + 3] = x.w;
+            }
+            // A operands of the scores: block b supplies k-steps b and b+16 (channels 4b.., 64+4b..) of head `row`
+            h4 qa[2];
+#pragma unroll
+            for (int i = 0; i < 2; i++) {
+                uint2 bits = {0u, 0u};
+                if (row < nheads) bits = *reinterpret_cast<const uint2 *>(a.q + (size_t)(bq0 + row) * kD + 4 * (blk4 + 16 * i));
+                const h2 lo = as_h2(bits.x), hi = as_h2(bits.y);
+                qa[i] = h4{lo[0], lo[1], hi[0], hi[1]};
+            }
+#pragma unroll
+            for (int i = 0; i < 16; i++)
+                *reinterpret_cast<uint4 *>(rows + (4 * i + rsub) * kKRowH + piece * 8) =
+                    uint4{g.v[4 * i], g.v[4 * i + 1], g.v[4 * i + 2], g.v[4 * i + 3]};
+            // the value rows are requested now and travel while the scores are computed
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const int rr = t0 + 4 * i + rsub;
+                const uint4 x = reinterpret_cast<const uint4 *>(Rv + (size_t)(rr < R ? rr : 0) * kD)[piece];
+                g.v[4 * i] = x.x; g.v[4 * i + 1] = x.y; g.v[4 * i + 2] = x.z; g.v[4 * i + 3] = x.w;
+            }
+            __builtin_amdgcn_wave_barrier();
+            QT_MARK(t_r1);
+            QT_ADD(16, t_r1 - t_r0);
+
+            f4 sc = {0.f, 0.f, 0.f, 0.f};                  // scores of token t0 + lane for the 4 heads
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const u4 kk = *reinterpret_cast<const u4 *>(rows + lane * kKRowH + i * 8);   // channels 8i..8i+7
+                const h2 k0 = as_h2(kk[0]), k1 = as_h2(kk[1]), k2 = as_h2(kk[2]), k3 = as_h2(kk[3]);
+                mfma_bc<4>(sc, qa[(2 * i) / 16], h4{k0[0], k0[1], k1[0], k1[1]}, (2 * i) % 16);
+                mfma_bc<4>(sc, qa[(2 * i + 1) / 16], h4{k2[0], k2[1], k3[0], k3[1]}, (2 * i + 1) % 16);
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int i = 0; i < 16; i++)
+                *reinterpret_cast<uint4 *>(rows + (4 * i + rsub) * kKRowH + piece * 8) =
+                    uint4{g.v[4 * i], g.v[4 * i + 1], g.v[4 * i + 2], g.v[4 * i + 3]};
+
+            QT_MARK(t_r2);
+            QT_ADD(17, t_r2 - t_r1);
+            // softmax update against the wave's state
+            float s[kNH], mn[kNH];
+            bool grow = false;
+#pragma unroll
+            for (int h = 0; h < kNH; h++) {
+                s[h] = valid ? sc[h] * a.c1 : -INFINITY;
+                mn[h] = s[h];
+            }
+            wave_max64x4(mn);
+#pragma unroll
+            for (int h = 0; h < kNH; h++) {
+                mn[h] = fmaxf(m[h], mn[h]);
+                grow |= mn[h] > m[h];
+            }
+            if (grow) {                                    // wave-uniform
+#pragma unroll
+                for (int h = 0; h < kNH; h++) {
+                    const float so = fast_exp2(m[h] - mn[h]);
+                    l_lane[h] *= so;
+                    O0[h] *= so;
+                    O1[h] *= so;
+#pragma unroll
+                    for (int gq = 0; gq < NCG; gq++) oz[h][gq] *= so;
+                    m[h] = mn[h];
+                }
+            }
+#pragma unroll
+            for (int h = 0; h < kNH; h++) {
+                const float p = fast_exp2(s[h] - m[h]);    // 0 past the end
+                l_lane[h] += p * fast_exp2(lg);            // the lane sums carry the factor 2^lg
+                pr[h * kPrH + lane] = (_Float16)p;
+            }
+            __builtin_amdgcn_wave_barrier();
+
+            QT_MARK(t_r3);
+            QT_ADD(18, t_r3 - t_r2);
+            // values: 16 k-steps of 4 tokens; block b supplies the weights of k-step b
+            const h4 pa = *reinterpret_cast<const h4 *>(pr + row * kPrH + 4 * blk4);
+            f4 R0 = {0.f, 0.f, 0.f, 0.f}, R1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 16; ks++) {
+                const _Float16 *v = rows + (4 * ks) * kKRowH + lane;
+                const h4 b0 = {v[0], v[kKRowH], v[2 * kKRowH], v[3 * kKRowH]};
+                const h4 b1 = {v[64], v[kKRowH + 64], v[2 * kKRowH + 64], v[3 * kKRowH + 64]};
+                mfma_bc<4>(R0, pa, b0, ks);
+                mfma_bc<4>(R1, pa, b1, ks);
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int h = 0; h < kNH; h++) {
+                O0[h] += R0[h] * (1.0f / vun);             // the state's outputs carry the factor 1/vun
+                O1[h] += R1[h] * (1.0f / vun);
+            }
+            QT_MARK(t_r4);
+            QT_ADD(19, t_r4 - t_r3);
+            QT_ADD(11, 1);
+        }
+        QT_MARK(t_u2);
+        QT_ADD(12, t_u2 - t_u1);
+
+        // =============================== quantized passes
+        float lsum[kNH];                                   // sum of weights (wave-uniform after the reduction)
+        float oa[kNH], ob[kNH];                            // un-normalised output of channels lane, lane+64
+        {
             // this lane's query values: head `row`, the channels of its k-steps, raw and pre-scaled by the
             // 4^-j of the code field (channel pair (c, c+1), c even, is field (c % 16) / 2 of its K word)
             h2 qraw[NKR][2], qscl[NKR][2];
 #pragma unroll
-            for (int i = 0; i < NKR; i++)
+            for (int i = 0; i < NKR; i++) {
+                const int c = 4 * (bbk + BGK * i);
+                uint2 bits = {0u, 0u};
+                if (row < nheads && j0 < j1) bits = *reinterpret_cast<const uint2 *>(a.q + (size_t)(bq0 + row) * kD + c);
+                qraw[i][0] = as_h2(bits.x);
+                qraw[i][1] = as_h2(bits.y);
 #pragma unroll
-                for (int ep = 0; ep < 2; ep++) {
-                    const int c = 4 * (bbk + BGK * i) + 2 * ep;
-                    uint32_t bits = 0;
-                    if (row < nheads) bits = *reinterpret_cast<const uint32_t *>(a.q + (size_t)(bq0 + row) * kD + c);
-                    qraw[i][ep] = as_h2(bits);
-                    qscl[i][ep] = qraw[i][ep] * (_Float16)fld_scale((c & 15) >> 1);
-                }
-
-            TL2(10);
-            float l_lane[kNH];
-            f4 O0 = {0.f, 0.f, 0.f, 0.f}, O1 = {0.f, 0.f, 0.f, 0.f};   // channel lane / lane+64, 4 heads each
-            float oz[kNH][NCG];
-#pragma unroll
-            for (int h = 0; h < kNH; h++) {
-                m[h] = -1e30f; l_lane[h] = 0.f;
-#pragma unroll
-                for (int g = 0; g < NCG; g++) oz[h][g] = 0.f;
+                for (int ep = 0; ep < 2; ep++)
+                    qscl[i][ep] = qraw[i][ep] * (_Float16)fld_scale(((c + 2 * ep) & 15) >> 1);
             }
-
-            auto load_k = [&](int tp) -> KD {
-                KD d;
-                const u4 *ktile = reinterpret_cast<const u4 *>(Kc + (size_t)(tp >> 7) * 1024);
-#pragma unroll
-                for (int i = 0; i < 4; i++) d.kw[i] = ktile[i * 64 + lane];
-                const bool gvalid = tp + gl * G < t_end;
-                const size_t go = ((size_t)(tp / G) + (gvalid ? gl : 0)) * kD + bbk * (NKR * 4);
-                d.ks = load_words<NKW>(Ks + go);
-                d.kz = load_words<NKW>(Kz + go);
-                return d;
-            };
-            auto load_v = [&](int tp) -> VD {
-                VD d;
-                const u4 *vtile = reinterpret_cast<const u4 *>(Vc + (size_t)(tp >> 6) * (4 * kD));
-#pragma unroll
-                for (int tl = 0; tl < 2; tl++) {
-                    d.vw[0][tl] = vtile[tl * kD + lane];
-                    d.vw[1][tl] = vtile[tl * kD + lane + 64];
-                }
-                // past the end the (clamped) load still happens and the value is masked to zero afterwards,
-                // so that the number of loads in flight is the same on every path
-                const bool valid = tp + 2 * lane < t_end;
-                const size_t vo = (size_t)(valid ? tp + 2 * lane : tp) * NCG;
-                d.vs = load_words<NCG>(Vs + vo);
-                d.vz = load_words<NCG>(Vz + vo);
-                return d;
-            };
 
             float s0[kNH], s1[kNH];                        // scores of the lane's two tokens
 
@@ -569,26 +558,23 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
                 __builtin_amdgcn_wave_barrier();
             };
 
-            // Loads run one phase ahead of their use and are issued on every path (the last iteration
-            // re-requests its own tile), so the number in flight is always the same.
-            {
-                auto tp_of = [&](int jj) { return (jj < j1 ? jj : j1 - 1) * kPass; };
-                KD kd = load_k(tp_of(j));
-                VD vd = load_v(tp_of(j));
-                TL(2);
-                for (int jj = j; jj < j1; jj++) {
-                    const int tp = jj * kPass;
-                    if (jj == j) TL2(11);
-                    k_phase(kd, tp);
-                    if (jj == j) TL2(12);
-                    kd = load_k(tp_of(jj + 1));
-                    v_phase(vd, tp);
-                    vd = load_v(tp_of(jj + 1));
-                }
+            QT_MARK(t_p0);
+            QT_ADD(4, t_p0 - t_u2);
+            // Loads run one phase ahead of their use and are issued on every path (the last pass requests its
+            // own tiles again), so the number in flight is always the same.
+            for (int jj = j0; jj < j1; jj++) {
+                const int tp = jj * kPass;
+                const int t2 = (jj + 1 < j1 ? jj + 1 : jj) * kPass;
+                k_phase(kd, tp);
+                kd = load_k(t2);
+                v_phase(vd, tp);
+                vd = load_v(t2);
             }
+            QT_MARK(t_p1);
+            QT_ADD(5, t_p1 - t_p0);
+            QT_ADD(10, j1 - j0);
 
-            TL(3);
-            // finish the segment: undo operand scalings, add the zero-point term
+            // finish: undo operand scalings, add the zero-point term
 #pragma unroll
             for (int h = 0; h < kNH; h++) lsum[h] = l_lane[h] * unlg;
             wave_sum64x4(lsum);
@@ -612,159 +598,44 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
                 oa[h] = O0[h] * vun + z0;
                 ob[h] = O1[h] * vun + z1;
             }
-            ca = lane; cb = lane + 64;
-        } else {
-            // =============================== residual items (64 fp16 tokens each) of unit u:
-            // Algorithm 1's R_K t_Q^T and A_unquant R_V on the vector ALU.  This path runs rarely, so it
-            // is written as compact loops (small code) around fully coalesced loads: the 64 key rows, then
-            // the 64 value rows, are fetched 4 rows per instruction (16 lanes x 16 B per row) and staged in
-            // LDS; lane = token for the scores, lane = channel pair for the values.
-            const int R = clampi(a.r_len[u], 0, a.Rcap);
-            _Float16 *qh = lds;                            // [kNH][128] halfs
-            _Float16 *rows = lds + kNH * kD;               // [64][kKRowH] halfs: key rows, then value rows
-            for (int i = lane; i < kNH * kD; i += 64) {
-                const int h = i / kD;
-                qh[i] = (h < nheads) ? __builtin_bit_cast(_Float16, a.q[(size_t)(bq0 + h) * kD + i % kD]) : (_Float16)0.f;
-            }
-            __builtin_amdgcn_wave_barrier();
-            const uint16_t *Rk = a.Rk + (size_t)u * a.Rcap * kD;
-            const uint16_t *Rv = a.Rv + (size_t)u * a.Rcap * kD;
-#pragma unroll
-            for (int h = 0; h < kNH; h++) { m[h] = -1e30f; lsum[h] = 0.f; oa[h] = 0.f; ob[h] = 0.f; }
-            TL(2);
-            const int rsub = lane >> 4, piece = lane & 15;  // row within a group of 4, 16-byte piece of the row
-
-#pragma unroll 1
-            for (int ri = r0; ri < r1; ri++) {
-                const int t0 = ri * 64;
-                const bool valid = t0 + lane < R;
-                if (ri == r0) TL2(0);
-                Words<64> g;
-#pragma unroll
-                for (int i = 0; i < 16; i++) {
-                    const int rr = t0 + 4 * i + rsub;
-                    const uint4 x = reinterpret_cast<const uint4 *>(Rk + (size_t)(rr < R ? rr : 0) * kD)[piece];
-                    g.v[4 * i] = x.x; g.v[4 * i + 1] = x.y; g.v[4 * i + 2] = x.z; g.v[4 * i + 3] = x.w;
-                }
-#pragma unroll
-                for (int i = 0; i < 16; i++)
-                    *reinterpret_cast<uint4 *>(rows + (4 * i + rsub) * kKRowH + piece * 8) =
-                        uint4{g.v[4 * i], g.v[4 * i + 1], g.v[4 * i + 2], g.v[4 * i + 3]};
-                // the value rows are requested now and travel while the scores are computed
-#pragma unroll
-                for (int i = 0; i < 16; i++) {
-                    const int rr = t0 + 4 * i + rsub;
-                    const uint4 x = reinterpret_cast<const uint4 *>(Rv + (size_t)(rr < R ? rr : 0) * kD)[piece];
-                    g.v[4 * i] = x.x; g.v[4 * i + 1] = x.y; g.v[4 * i + 2] = x.z; g.v[4 * i + 3] = x.w;
-                }
-                __builtin_amdgcn_wave_barrier();
-                if (ri == r0) TL2(1);
-
-                float acc[kNH] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-                for (int i = 0; i < 16; i++) {
-                    const u4 kk = *reinterpret_cast<const u4 *>(rows + lane * kKRowH + i * 8);
-#pragma unroll
-                    for (int h = 0; h < kNH; h++) {
-                        const u4 qq = *reinterpret_cast<const u4 *>(qh + h * kD + i * 8);
-#pragma unroll
-                        for (int p = 0; p < 4; p++)
-                            acc[h] = __builtin_amdgcn_fdot2(as_h2(qq[p]), as_h2(kk[p]), acc[h], false);
-                    }
-                }
-                __builtin_amdgcn_wave_barrier();
-                if (ri == r0) TL2(2);
-#pragma unroll
-                for (int i = 0; i < 16; i++)
-                    *reinterpret_cast<uint4 *>(rows + (4 * i + rsub) * kKRowH + piece * 8) =
-                        uint4{g.v[4 * i], g.v[4 * i + 1], g.v[4 * i + 2], g.v[4 * i + 3]};
-                if (ri == r0) TL2(3);
-
-                float mn[kNH];
-                bool grow = false;
-#pragma unroll
-                for (int h = 0; h < kNH; h++) {
-                    acc[h] = valid ? acc[h] * a.c1 : -INFINITY;
-                    mn[h] = acc[h];
-                }
-                wave_max64x4(mn);
-#pragma unroll
-                for (int h = 0; h < kNH; h++) {
-                    mn[h] = fmaxf(m[h], mn[h]);
-                    grow |= mn[h] > m[h];
-                }
-                if (grow) {
-#pragma unroll
-                    for (int h = 0; h < kNH; h++) {
-                        const float sc = fast_exp2(m[h] - mn[h]);
-                        lsum[h] *= sc; oa[h] *= sc; ob[h] *= sc;
-                        m[h] = mn[h];
-                    }
-                }
-                float pr[kNH];                             // weight of this lane's token (0 past the end)
-#pragma unroll
-                for (int h = 0; h < kNH; h++) {
-                    pr[h] = fast_exp2(acc[h] - m[h]);
-                    lsum[h] += pr[h];
-                }
-                __builtin_amdgcn_wave_barrier();
-                if (ri == r0) TL2(4);
-                // values: the weight of token tt is read from lane tt (wave-uniform operand)
-#pragma unroll 16
-                for (int tt = 0; tt < 64; tt++) {
-                    const h2 v = as_h2(*reinterpret_cast<const uint32_t *>(rows + tt * kKRowH + 2 * lane));
-                    const float v0 = (float)v[0], v1 = (float)v[1];
-#pragma unroll
-                    for (int h = 0; h < kNH; h++) {
-                        const float ph = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, pr[h]), tt));
-                        oa[h] += ph * v0;
-                        ob[h] += ph * v1;
-                    }
-                }
-                __builtin_amdgcn_wave_barrier();
-                if (ri == r0) TL2(5);
-            }
-            TL(3);
-            wave_sum64x4(lsum);
-            ca = 2 * lane; cb = 2 * lane + 1;
+            QT_MARK(t_p2);
+            QT_ADD(6, t_p2 - t_p1);
         }
 
-        TL(4);
-#ifdef MINIKV_TIMELINE
-        if (lane == 0) g_timeline[(size_t)(blockIdx.x % 16384) * 8 + 7] = kind * 1000 + expected;
-#endif
-        // =============================== publish the segment
+        // =============================== publish this wave's partial of the unit
+        QT_MARK(t_b0);
         if (expected == 1) {
-            // the only segment of its unit: normalise and write the result directly
+            // the only partial of its unit: normalise and write the result directly
 #pragma unroll
             for (int h = 0; h < kNH; h++) {
                 if (h < nheads) {
                     const float inv = lsum[h] > 0.f ? 1.0f / lsum[h] : 0.f;
-                    a.out[(size_t)(bq0 + h) * kD + ca] = __half_as_ushort(__float2half_rn(oa[h] * inv));
-                    a.out[(size_t)(bq0 + h) * kD + cb] = __half_as_ushort(__float2half_rn(ob[h] * inv));
+                    a.out[(size_t)(bq0 + h) * kD + lane] = __half_as_ushort(__float2half_rn(oa[h] * inv));
+                    a.out[(size_t)(bq0 + h) * kD + lane + 64] = __half_as_ushort(__float2half_rn(ob[h] * inv));
                 }
             }
         } else {
-            const int slot = w + 2 * up + kind;
+            const int slot = w + 2 * up;
 #pragma unroll
             for (int h = 0; h < kNH; h++) {
                 if (h < nheads) {
                     float *pp = slot_ptr(a, slot, h);
-                    st_agent(pp + 4 + ca, oa[h]);
-                    st_agent(pp + 4 + cb, ob[h]);
+                    st_agent(pp + 4 + lane, oa[h]);
+                    st_agent(pp + 4 + lane + 64, ob[h]);
                     if (lane == 0) { st_agent(pp, m[h]); st_agent(pp + 1, lsum[h]); }
                 }
             }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // all stores acknowledged ...
             int old = 0;
             if (lane == 0) old = atomicAdd(a.cnt + up, 1);           // ... before the ticket is taken
-            old = __shfl(old, 0);
+            old = __builtin_amdgcn_readfirstlane(old);
+            QT_MARK(t_b1);
+            QT_ADD(7, t_b1 - t_b0);
             if (old == expected - 1) {
-                // last segment of the unit to arrive: merge all partials, write the output.  Lane s fetches
-                // (max, sum) of segment s, which gives every segment's weight; the output vectors (channels
-                // 2*lane, 2*lane+1 per lane) of up to 16 segments are requested in the same round trip.
-                const int nsq = wq1 - wq0 + 1;
-                auto slot_of = [&](int sg) { return sg < nsq ? wq0 + sg + 2 * up : wr0 + (sg - nsq) + 2 * up + 1; };
+                // last partial of the unit to arrive: merge them all, write the output.  Lane s fetches
+                // (max, sum) of partial s, which gives every partial's weight; the output vectors (channels
+                // 2*lane, 2*lane+1 per lane) of up to 16 partials are requested in the same round trip.
+                auto slot_of = [&](int sg) { return wf + sg + 2 * up; };
                 float M[kNH], L[kNH], Oa[kNH], Ob[kNH];
 #pragma unroll
                 for (int h = 0; h < kNH; h++) { M[h] = -1e30f; L[h] = 0.f; Oa[h] = 0.f; Ob[h] = 0.f; }
@@ -824,24 +695,19 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
                     *reinterpret_cast<uint32_t *>(a.out + (size_t)(bq0 + h) * kD + 2 * lane) = as_u32(r);
                 }
                 if (lane == 0) a.cnt[up] = 0;              // ready for the next call
+                QT_MARK(t_b2);
+                QT_ADD(8, t_b2 - t_b1);
+                QT_ADD(14, 1);
             }
         }
-      }   // kind
+        QT_ADD(9, 1);
         ib = ib_next;
     }
-    TL(5);
-}
-
 #ifdef MINIKV_TIMELINE
-extern "C" int minikv_debug_timeline(long long *host, int n)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_timeline), (size_t)n * 8, 0, hipMemcpyDeviceToHost);
-}
-extern "C" int minikv_debug_timeline2(long long *host, int n)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_tl2), (size_t)n * 8, 0, hipMemcpyDeviceToHost);
-}
+    QT_SET(1, __builtin_amdgcn_s_memrealtime());
+    QT_SET(15, QT_NOW() - t_begin);
 #endif
+}
 
 template <int G, bool LO>
 static int launch_stream(DecArgs a, hipStream_t st)
