@@ -91,9 +91,9 @@ size_t minikv_workspace_bytes(const minikv_shape *s)
     // cross-check kernel: one partial per (query row, chunk) for the smallest chunk, plus the residual chunk
     const size_t nch = (size_t)(s->Tcap + kMinChunk - 1) / kMinChunk + 1;
     const size_t scalar = (size_t)s->B * s->Hq * nch * kPartialStride * sizeof(float);
-    // single-launch kernel: one slot of 4 heads per (wave, unit it serves) and per residual item
+    // single-launch kernel: one slot of 4 heads per (wave, unit it serves): slot = wave + 2 * unit
     const size_t nu = ws_units(*s);
-    const size_t stream = ((size_t)kMaxStreamWaves + 2 * nu + nu * ((s->Rcap + 63) / 64)) * 4 * kPartialStride * sizeof(float);
+    const size_t stream = ((size_t)kMaxStreamWaves + 2 * nu) * 4 * kPartialStride * sizeof(float);
     return ws_counter_bytes(*s) + (scalar > stream ? scalar : stream);
 }
 

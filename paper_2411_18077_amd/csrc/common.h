@@ -17,14 +17,14 @@ constexpr int kMaxRep = 8;         // most query heads per KV head
 constexpr int kMaxStreamWaves = 4096;  // most single-wave workgroups the decode kernel is launched with
 
 // Workspace layout of the single-launch decode kernel: per (unit, set of 4 query heads) a ticket counter
-// and an item counter (zero between calls), then the split-K partials.
+// (zero between calls), then the split-K partials.
 __host__ __device__ inline size_t ws_units(const minikv_shape &s)
 {
     return (size_t)s.B * s.Hkv * ((s.Hq / s.Hkv + 3) / 4);
 }
 __host__ __device__ inline size_t ws_counter_bytes(const minikv_shape &s)
 {
-    return (2 * ws_units(s) * sizeof(int) + 255) / 256 * 256;
+    return (ws_units(s) * sizeof(int) + 255) / 256 * 256;
 }
 
 // per-unit element counts

@@ -196,9 +196,8 @@ int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache
     a.q = q; a.Kc = c.Kc; a.Vc = c.Vc; a.Ks = c.Ks; a.Kz = c.Kz; a.Vs = c.Vs; a.Vz = c.Vz;
     a.Rk = c.Rk; a.Rv = c.Rv; a.q_len = c.q_len; a.r_len = c.r_len;
     a.out = out;
+    a.first_slot = 0;
     a.cnt = reinterpret_cast<int *>(workspace);
-    a.qcnt = a.cnt + ws_units(s);
-    a.nri = (s.Rcap + 63) / 64;
     a.ws = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + ws_counter_bytes(s));
     a.c1 = sm_scale * 1.44269504088896340736f;
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.rep = g.rep; a.Tcap = s.Tcap; a.Rcap = s.Rcap;

@@ -38,16 +38,18 @@
 namespace minikv {
 
 // ------------------------------------------------------------------------------------------------
-// Work distribution.  Every unit (batch, KV head, set of 4 query heads) has ceil(R/64) residual items
-// followed by ceil(T/128) quantized passes.  The units' weights (kWR per residual item, kWQ per pass) are
-// laid end to end and the line is cut into NW equal ranges, one per wave; a wave owns the items that
-// START inside its range, so ragged lengths are balanced by construction.  What a wave does for one unit
+// Work distribution.  Every unit (batch, KV head, set of 4 query heads) has ceil(R/64) residual items and
+// ceil(T/128) quantized passes; its span of the weight line holds the even residual items, the passes,
+// then the odd residual items (so that the usual two items fall to two different waves).  The units'
+// spans (kWR per residual item, kWQ per pass) are laid end to end and the line is cut into NW equal
+// ranges, one per wave; a wave owns the items that START inside its range, so ragged lengths are balanced
+// by construction.  What a wave does for one unit
 // ends in one split-K partial (running max, sum, un-normalised output); the partial that arrives last at
 // its unit (device-scope ticket counter) merges the unit's partials and writes the fp16 output, so one
 // kernel launch does the whole call.  (Drawing passes from a per-unit counter instead was tried: a vector
 // atomic per pass, even one whose result is needed a full pass later, slowed the pass loop by 40 %.)
 struct UnitItems { int nq, nr, T, R; };
-constexpr int kWQ = 2, kWR = 5;        // relative cost of a quantized pass (128 tokens, 12 KB) and a residual
+constexpr int kWQ = 2, kWR = 7;        // relative cost of a quantized pass (128 tokens, 12 KB) and a residual
                                        // item (64 fp16 tokens, 32 KB), measured
 
 __device__ inline UnitItems unit_items(const DecArgs &a, int up)
@@ -92,8 +94,8 @@ __device__ inline float *slot_ptr(const DecArgs &a, int slot, int h)
 #ifdef MINIKV_TIMELINE
 __device__ long long g_qtl[16384 * 24];
 #define QT_NOW() __builtin_readcyclecounter()
-#define QT_SET(slot, v) do { if (threadIdx.x == 0) g_qtl[(size_t)(blockIdx.x % 16384) * 24 + (slot)] = (v); } while (0)
-#define QT_ADD(slot, v) do { if (threadIdx.x == 0) g_qtl[(size_t)(blockIdx.x % 16384) * 24 + (slot)] += (v); } while (0)
+#define QT_SET(slot, v) do { qt[slot] = (long long)(v); } while (0)
+#define QT_ADD(slot, v) do { qt[slot] += (long long)(v); } while (0)
 #define QT_MARK(var) const long long var = QT_NOW()
 extern "C" int minikv_debug_qtl(long long *host, int n)
 {
@@ -125,66 +127,97 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
     const int lane = threadIdx.x;
     const int NU = a.units * a.hsets;
 #ifdef MINIKV_TIMELINE
-    for (int i = 2; i < 24; i++) QT_SET(i, 0);
+    long long qt[24];                                      // kept in registers, written once at the end
+    for (int i = 0; i < 24; i++) qt[i] = 0;
     QT_SET(0, __builtin_amdgcn_s_memrealtime());
     { unsigned hwid, xcc; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid)); asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc)); QT_SET(13, (long long)hwid | ((long long)xcc << 32)); }
 #endif
     QT_MARK(t_begin);
 
-    // ---------------- total weight of all items; units without any token get their zeros here
-    auto unit_weight = [&](int uu) -> int {
-        if (uu >= NU) return 0;
-        const UnitItems it = unit_items(a, uu);
-        return kWQ * it.nq + kWR * it.nr;
+    // ---------------- the work list: total weight P, this wave's range, the unit that holds its start.
+    // Lane l looks at units l, l+64, ...; up to 256 units the lengths stay in registers between the two
+    // steps (sum, then locate), beyond that the second step reads them again.  Units without any token
+    // get their zeros here.
+    auto zero_fill = [&](int uu) {
+        const int u = uu >> a.hs_shift, hs = uu & (a.hsets - 1);
+        const int bi = (int)fast_div((uint32_t)u, a.hkv_magic, a.hkv_shift);
+        const int bq0 = bi * a.Hq + (u - bi * a.Hkv) * a.rep + hs * kNH;
+        const int nh = min(kNH, a.rep - hs * kNH);
+        for (int i = 0; i < nh * kD; i++) a.out[(size_t)bq0 * kD + i] = 0;
     };
-    int mine = 0;
+    auto lengths_of = [&](int uu, int &T, int &R) {        // branch-free so that the loads go out together
+        const int u = min(uu, NU - 1) >> a.hs_shift;
+        const int t = a.q_len[u], r = a.r_len[u];
+        T = uu < NU ? clampi(t, 0, a.Tcap) : 0;
+        R = uu < NU ? clampi(r, 0, a.Rcap) : 0;
+    };
+    auto weight_of = [&](int T, int R) -> int { return kWQ * ((T + kPass - 1) / kPass) + kWR * ((R + 63) >> 6); };
+    const bool small = NU <= 256;
+    int Tl[4], Rl[4], wl4[4], incl4[4];
+    int P = 0;
     for (int base = 0; base < NU; base += 256) {
-        int n[4];
 #pragma unroll
-        for (int k = 0; k < 4; k++) n[k] = unit_weight(base + 64 * k + lane);
+        for (int k = 0; k < 4; k++) lengths_of(base + 64 * k + lane, Tl[k], Rl[k]);
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             const int uu = base + 64 * k + lane;
-            mine += n[k];
-            if (uu < NU && n[k] == 0 && uu % (int)gridDim.x == (int)blockIdx.x) {
-                const int u = uu >> a.hs_shift, hs = uu & (a.hsets - 1);
-                const int bi = (int)fast_div((uint32_t)u, a.hkv_magic, a.hkv_shift);
-                const int bq0 = bi * a.Hq + (u - bi * a.Hkv) * a.rep + hs * kNH;
-                const int nh = min(kNH, a.rep - hs * kNH);
-                for (int i = 0; i < nh * kD; i++) a.out[(size_t)bq0 * kD + i] = 0;
-            }
+            wl4[k] = weight_of(Tl[k], Rl[k]);
+            if (uu < NU && wl4[k] == 0 && uu % (int)gridDim.x == (int)blockIdx.x) zero_fill(uu);
+            incl4[k] = wave_scan_i32(wl4[k]);
+            P += __builtin_amdgcn_readlane(incl4[k], 63);
         }
     }
-    const int P = wave_sum_i32(mine);
-    // The weight line is cut into NW ranges, each at least one residual item long.  NW is a power of two
-    // so that the cuts need no division.
+    QT_MARK(t_sum);
+    QT_ADD(22, t_sum - t_begin);
+    // The weight line is cut into NW ranges, each at least one residual item long.  NW is a power of two so
+    // that the cuts need no division.
     if (P == 0) return;
     const int nw_cap = max(1, min((int)gridDim.x, P / kWR));
     const int nw_log = 31 - __builtin_clz(nw_cap), NW = 1 << nw_log;
-    const int w = blockIdx.x;
-    if (w >= NW) return;
+    if ((int)blockIdx.x >= NW) return;
+    // Wave numbers.  The hardware serves the older of the two waves on a SIMD first, so the workgroups
+    // that were dispatched first (they fill the first wave slot of every SIMD, a.first_slot of them) get
+    // through their passes measurably faster than the rest.  When the launch fills both slots, workgroup b
+    // and workgroup b + a.first_slot take the neighbouring numbers 2b and 2b + 1, so that every unit is
+    // served by both kinds in equal parts and all units finish together.
+    const bool paired = NW == 2 * a.first_slot;
+    const int w = !paired ? (int)blockIdx.x
+                : (int)blockIdx.x < a.first_slot ? 2 * (int)blockIdx.x : 2 * ((int)blockIdx.x - a.first_slot) + 1;
     const long start = range_start(w, P, nw_log), end = range_start(w + 1, P, nw_log);
     const float inv_p = 1.0f / (float)P;
 
     // ---------------- the unit whose weight span holds position `start`
     int up = -1;
     long ib = 0;                                           // position of the unit's first item
+    int T_first = 0, R_first = 0;                          // its lengths
     {
         long running = 0;
-        for (int base = 0; base < NU && up < 0; base += 64) {
-            const int n = unit_weight(base + lane);
-            const int incl = wave_scan_i32(n);
-            const long excl = running + incl - n;
-            const bool hit = n > 0 && start >= excl && start < excl + n;
-            const unsigned long long mask = __ballot(hit);
-            if (mask) {
-                const int src = __ffsll((long long)mask) - 1;
-                up = base + src;
-                ib = running + __shfl(incl - n, src);
+        for (int base = 0; base < NU && up < 0; base += 256) {
+            if (!small) {
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    lengths_of(base + 64 * k + lane, Tl[k], Rl[k]);
+                    wl4[k] = weight_of(Tl[k], Rl[k]);
+                    incl4[k] = wave_scan_i32(wl4[k]);
+                }
             }
-            running += __builtin_amdgcn_readlane(incl, 63);
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                const long excl = running + incl4[k] - wl4[k];
+                const bool hit = up < 0 && wl4[k] > 0 && start >= excl && start < excl + wl4[k];
+                const unsigned long long mask = __ballot(hit);
+                if (mask) {
+                    const int src = __ffsll((long long)mask) - 1;
+                    up = base + 64 * k + src;
+                    ib = running + __builtin_amdgcn_readlane(incl4[k] - wl4[k], src);
+                    T_first = __builtin_amdgcn_readlane(Tl[k], src);
+                    R_first = __builtin_amdgcn_readlane(Rl[k], src);
+                }
+                running += __builtin_amdgcn_readlane(incl4[k], 63);
+            }
         }
     }
+    const int up_first = up;
     QT_MARK(t_prol);
     QT_ADD(2, t_prol - t_begin);
 
@@ -206,22 +239,22 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
     // A wave owns the items whose start position lies in [start, end).
     for (; up < NU && ib < end; up++) {
         QT_MARK(t_u0);
-        const UnitItems it = unit_items(a, up);
+        // (the lengths of the first unit are already known)
+        const UnitItems it = up == up_first ? UnitItems{(T_first + kPass - 1) / kPass, (R_first + 63) / 64, T_first, R_first}
+                                            : unit_items(a, up);
         const int wt = kWR * it.nr + kWQ * it.nq;
         if (wt == 0) continue;
         const long ib_next = ib + wt;
         // this wave's items of the unit (the offsets are clamped to the unit's span first, so 32-bit
-        // arithmetic suffices): residual items r0..r1-1, passes j0..j1-1
+        // arithmetic suffices): front residual items f0..f1-1, passes j0..j1-1, back residual items b0..b1-1
+        const int nf = (it.nr + 1) >> 1, nb = it.nr >> 1;
         const int span = wt + kWR;
         const int ds = (int)min((long)span, max(0L, start - ib)), de = (int)min((long)span, max(0L, end - ib));
-        const int dq = kWR * it.nr;
-        const int r0 = min(it.nr, (ds + kWR - 1) / kWR), r1 = min(it.nr, (de + kWR - 1) / kWR);
+        const int dq = kWR * nf, db = dq + kWQ * it.nq;
+        const int f0 = min(nf, (ds + kWR - 1) / kWR), f1 = min(nf, (de + kWR - 1) / kWR);
         const int j0 = min(it.nq, (max(0, ds - dq) + kWQ - 1) / kWQ), j1 = min(it.nq, (max(0, de - dq) + kWQ - 1) / kWQ);
-        if (r0 >= r1 && j0 >= j1) { ib = ib_next; continue; }
-        // the waves that own items of this unit: from the owner of the first item to the owner of the last
-        const int wf = wave_of(ib, P, nw_log, inv_p);
-        const int wl = wave_of(ib_next - (it.nq ? kWQ : kWR), P, nw_log, inv_p);
-        const int expected = wl - wf + 1;
+        const int b0 = min(nb, (max(0, ds - db) + kWR - 1) / kWR), b1 = min(nb, (max(0, de - db) + kWR - 1) / kWR);
+        if (f0 >= f1 && j0 >= j1 && b0 >= b1) { ib = ib_next; continue; }
         const int u = up >> a.hs_shift, hs = up & (a.hsets - 1);
         const int bi = (int)fast_div((uint32_t)u, a.hkv_magic, a.hkv_shift);
         const int bq0 = bi * a.Hq + (u - bi * a.Hkv) * a.rep + hs * kNH;
@@ -290,8 +323,12 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
         // read back as the B operand, q as the A operand broadcast to all 16 blocks.  Values: lane =
         // channels lane, lane+64, the B operand gathered token by token from the staged rows, the weights
         // p (fp16, through LDS) as the broadcast A operand.  The result is folded into the wave's state.
+        float lsum[kNH];                                   // sum of weights (wave-uniform after the reduction)
+        float oa[kNH], ob[kNH];                            // un-normalised output of channels lane, lane+64
+        auto residual_items = [&](int lo, int hi, int odd) {   // even items sit before the passes, odd ones after
 #pragma unroll 1
-        for (int ri = r0; ri < r1; ri++) {
+        for (int fi = lo; fi < hi; fi++) {
+            const int ri = 2 * fi + odd;
             const int R = it.R;
             _Float16 *pr = lds;                            // [kNH][64 + 8] halfs: weights of the item's tokens
             _Float16 *rows = lds + kNH * kD;               // [64][kKRowH] halfs: key rows, then value rows
@@ -407,13 +444,12 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
             QT_ADD(19, t_r4 - t_r3);
             QT_ADD(11, 1);
         }
+        };
+        residual_items(f0, f1, 0);
+        {
+        // =============================== quantized passes
         QT_MARK(t_u2);
         QT_ADD(12, t_u2 - t_u1);
-
-        // =============================== quantized passes
-        float lsum[kNH];                                   // sum of weights (wave-uniform after the reduction)
-        float oa[kNH], ob[kNH];                            // un-normalised output of channels lane, lane+64
-        {
             // this lane's query values: head `row`, the channels of its k-steps, raw and pre-scaled by the
             // 4^-j of the code field (channel pair (c, c+1), c even, is field (c % 16) / 2 of its K word)
             h2 qraw[NKR][2], qscl[NKR][2];
@@ -573,7 +609,11 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
             QT_MARK(t_p1);
             QT_ADD(5, t_p1 - t_p0);
             QT_ADD(10, j1 - j0);
+        }
+        residual_items(b0, b1, 1);
 
+        {
+            QT_MARK(t_p1);
             // finish: undo operand scalings, add the zero-point term
 #pragma unroll
             for (int h = 0; h < kNH; h++) lsum[h] = l_lane[h] * unlg;
@@ -603,6 +643,10 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
         }
 
         // =============================== publish this wave's partial of the unit
+        // the waves that own items of this unit: from the owner of the first item to the owner of the last
+        const int wf = wave_of(ib, P, nw_log, inv_p);
+        const int wl = wave_of(ib_next - (nb ? kWR : it.nq ? kWQ : kWR), P, nw_log, inv_p);
+        const int expected = wl - wf + 1;
         QT_MARK(t_b0);
         if (expected == 1) {
             // the only partial of its unit: normalise and write the result directly
@@ -635,7 +679,12 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
                 // last partial of the unit to arrive: merge them all, write the output.  Lane s fetches
                 // (max, sum) of partial s, which gives every partial's weight; the output vectors (channels
                 // 2*lane, 2*lane+1 per lane) of up to 16 partials are requested in the same round trip.
-                auto slot_of = [&](int sg) { return wf + sg + 2 * up; };
+                // The group's slots are consecutive; all addresses are a wave-uniform base plus constants, so
+                // that the loads cost one instruction each (the merge runs alone on its SIMD at the end of
+                // the launch and is bound by instruction issue).
+                const char *const sbase = reinterpret_cast<const char *>(slot_ptr(a, wf + 2 * up, 0));
+                constexpr int kSlotB = kNH * kPartialStride * 4, kHeadB = kPartialStride * 4;
+                const int lane8 = lane * 8;
                 float M[kNH], L[kNH], Oa[kNH], Ob[kNH];
 #pragma unroll
                 for (int h = 0; h < kNH; h++) { M[h] = -1e30f; L[h] = 0.f; Oa[h] = 0.f; Ob[h] = 0.f; }
@@ -643,23 +692,24 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
 #pragma unroll 1
                 for (int base = 0; base < expected; base += MB) {
                     const int cnt = min(MB, expected - base);
-                    const int sg = base + lane;
                     const bool has = lane < cnt;
-                    const int my_slot = slot_of(has ? sg : base);
+                    // lane s: (max, sum) of partial base+s for every head
+                    const char *const mine_p = sbase + (size_t)(base + (has ? lane : 0)) * kSlotB;
                     float ms[kNH], ls[kNH], cm[kNH];
 #pragma unroll
                     for (int h = 0; h < kNH; h++) {
-                        const float2 ml = ld_agent2(slot_ptr(a, my_slot, h < nheads ? h : 0));
+                        const float2 ml = ld_agent2(reinterpret_cast<const float *>(mine_p + h * kHeadB));
                         const bool on = has && h < nheads;
-                        ms[h] = on ? ml.x : -1e30f;
+                        ms[h] = on ? ml.x : -1e30f;        // partials that do not exist get weight 0 below
                         ls[h] = on ? ml.y : 0.f;
                     }
                     float2 x[MB][kNH];
 #pragma unroll
                     for (int k = 0; k < MB; k++) {
-                        const int sl = slot_of(base + (k < cnt ? k : 0));      // clamped; weight zeroed below
+                        const char *const pk = sbase + (size_t)(base + min(k, cnt - 1)) * kSlotB;   // uniform
 #pragma unroll
-                        for (int h = 0; h < kNH; h++) x[k][h] = ld_agent2(slot_ptr(a, sl, h < nheads ? h : 0) + 4 + 2 * lane);
+                        for (int h = 0; h < kNH; h++)
+                            x[k][h] = ld_agent2(reinterpret_cast<const float *>(pk + h * kHeadB + 16 + lane8));
                     }
 #pragma unroll
                     for (int h = 0; h < kNH; h++) cm[h] = ms[h];
@@ -669,7 +719,7 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
                     for (int h = 0; h < kNH; h++) {
                         const float Mn = fmaxf(M[h], cm[h]);
                         const float so = fast_exp2(M[h] - Mn);
-                        wgt[h] = fast_exp2(ms[h] - Mn);
+                        wgt[h] = fast_exp2(ms[h] - Mn);    // exactly 0 for ms = -1e30
                         lw[h] = ls[h] * wgt[h];
                         L[h] *= so; Oa[h] *= so; Ob[h] *= so;
                         M[h] = Mn;
@@ -677,14 +727,15 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
                     wave_sum64x4(lw);
 #pragma unroll
                     for (int h = 0; h < kNH; h++) L[h] += lw[h];
+                    QT_MARK(t_m1);
+                    QT_ADD(20, t_m1 - t_b1);
 #pragma unroll
                     for (int k = 0; k < MB; k++)
 #pragma unroll
                         for (int h = 0; h < kNH; h++) {
                             const float wl = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wgt[h]), k));
-                            const float wv = (k < cnt && h < nheads) ? wl : 0.f;
-                            Oa[h] += x[k][h].x * wv;
-                            Ob[h] += x[k][h].y * wv;
+                            Oa[h] += x[k][h].x * wl;
+                            Ob[h] += x[k][h].y * wl;
                         }
                 }
 #pragma unroll
@@ -696,6 +747,7 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
                 }
                 if (lane == 0) a.cnt[up] = 0;              // ready for the next call
                 QT_MARK(t_b2);
+                QT_ADD(21, t_b2 - t_b1);
                 QT_ADD(8, t_b2 - t_b1);
                 QT_ADD(14, 1);
             }
@@ -706,6 +758,8 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
 #ifdef MINIKV_TIMELINE
     QT_SET(1, __builtin_amdgcn_s_memrealtime());
     QT_SET(15, QT_NOW() - t_begin);
+    if (threadIdx.x == 0)
+        for (int i = 0; i < 24; i++) g_qtl[(size_t)(blockIdx.x % 16384) * 24 + i] = qt[i];
 #endif
 }
 
@@ -731,6 +785,10 @@ static int launch_stream(DecArgs a, hipStream_t st)
     long nw = resident < kMaxStreamWaves ? resident : kMaxStreamWaves;
     if (nw > cap_items) nw = cap_items;
     if (nw < 1) nw = 1;
+    a.first_slot = resident / 2;
+#ifdef MINIKV_TIMELINE
+    if (const char *e = getenv("MINIKV_NW")) nw = atol(e);
+#endif
     hipLaunchKernelGGL(kern, dim3((unsigned)nw), dim3(64), lds_bytes, st, a);
     return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
 }
