@@ -189,20 +189,24 @@ __global__ void update_lengths_kernel(QuantArgs a, int units)
     if (a.flush) a.r_len[u] = 0;
 }
 
+// One workgroup of 64 threads per group of 2 units: thread = (unit, K or V, 16-byte piece).  The new rows
+// are requested together with the length, so the kernel costs one memory round trip plus the store.
 __global__ __launch_bounds__(64) void append_residual_kernel(const uint16_t *k_new, const uint16_t *v_new,
                                                              uint16_t *Rk, uint16_t *Rv, int32_t *r_len,
-                                                             int Rcap)
+                                                             int Rcap, int units)
 {
-    const int u = blockIdx.x, tid = threadIdx.x;
+    const int tid = threadIdx.x;
+    const int u = blockIdx.x * 2 + (tid >> 5);
+    if (u >= units) return;
+    const int which = (tid >> 4) & 1, piece = tid & 15;
+    const uint4 row = reinterpret_cast<const uint4 *>((which ? v_new : k_new) + (size_t)u * kD)[piece];
     const int r = r_len[u];
-    __syncthreads();                                   // everyone has read r before it is bumped
     if (r < 0 || r >= Rcap) return;
-    if (tid < 32) {
-        const uint16_t *src = (tid < 16 ? k_new : v_new) + (size_t)u * kD;
-        uint16_t *dst = (tid < 16 ? Rk : Rv) + ((size_t)u * Rcap + r) * kD;
-        reinterpret_cast<uint4 *>(dst)[tid & 15] = reinterpret_cast<const uint4 *>(src)[tid & 15];
-    }
-    if (tid == 0) r_len[u] = r + 1;
+    uint16_t *dst = (which ? Rv : Rk) + ((size_t)u * Rcap + r) * kD;
+    reinterpret_cast<uint4 *>(dst)[piece] = row;
+    // every thread of the unit has its r in a register by now (the loads above were waited for), so the
+    // length can be bumped without a barrier
+    if ((tid & 31) == 0) r_len[u] = r + 1;
 }
 
 template <int G>
@@ -237,8 +241,9 @@ int launch_quantize(const minikv_shape &s, const minikv_f16 *K, const minikv_f16
 int launch_append(const minikv_shape &s, const minikv_f16 *k_new, const minikv_f16 *v_new,
                   const minikv_cache &c, hipStream_t st)
 {
-    hipLaunchKernelGGL(append_residual_kernel, dim3(s.B * s.Hkv), dim3(64), 0, st, k_new, v_new, c.Rk,
-                       c.Rv, c.r_len, s.Rcap);
+    const int units = s.B * s.Hkv;
+    hipLaunchKernelGGL(append_residual_kernel, dim3((units + 1) / 2), dim3(64), 0, st, k_new, v_new, c.Rk,
+                       c.Rv, c.r_len, s.Rcap, units);
     return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
 }
 
