@@ -143,28 +143,45 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
         const int bi = (int)fast_div((uint32_t)u, a.hkv_magic, a.hkv_shift);
         const int bq0 = bi * a.Hq + (u - bi * a.Hkv) * a.rep + hs * kNH;
         const int nh = min(kNH, a.rep - hs * kNH);
-        for (int i = 0; i < nh * kD; i++) a.out[(size_t)bq0 * kD + i] = 0;
+        for (int i = lane; i < nh * kD; i += 64) a.out[(size_t)bq0 * kD + i] = 0;   // the whole wave
     };
-    auto lengths_of = [&](int uu, int &T, int &R) {        // branch-free so that the loads go out together
-        const int u = min(uu, NU - 1) >> a.hs_shift;
-        const int t = a.q_len[u], r = a.r_len[u];
-        T = uu < NU ? clampi(t, 0, a.Tcap) : 0;
-        R = uu < NU ? clampi(r, 0, a.Rcap) : 0;
+    // lengths of units base + 64k + lane, k = 0..3: all eight loads go out before any is waited for
+    auto lengths4 = [&](int base, int (&T)[4], int (&R)[4]) {
+        int t[4], r[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const int u = min(base + 64 * k + lane, NU - 1) >> a.hs_shift;
+            t[k] = a.q_len[u];
+            r[k] = a.r_len[u];
+        }
+        asm volatile("" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]), "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]));
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const bool in = base + 64 * k + lane < NU;
+            T[k] = in ? clampi(t[k], 0, a.Tcap) : 0;
+            R[k] = in ? clampi(r[k], 0, a.Rcap) : 0;
+        }
     };
     auto weight_of = [&](int T, int R) -> int { return kWQ * ((T + kPass - 1) / kPass) + kWR * ((R + 63) >> 6); };
     const bool small = NU <= 256;
     int Tl[4], Rl[4], wl4[4], incl4[4];
     int P = 0;
+    bool empties = false;                                  // some unit of this wave's share holds no token
     for (int base = 0; base < NU; base += 256) {
-#pragma unroll
-        for (int k = 0; k < 4; k++) lengths_of(base + 64 * k + lane, Tl[k], Rl[k]);
+        lengths4(base, Tl, Rl);
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             const int uu = base + 64 * k + lane;
             wl4[k] = weight_of(Tl[k], Rl[k]);
-            if (uu < NU && wl4[k] == 0 && uu % (int)gridDim.x == (int)blockIdx.x) zero_fill(uu);
+            empties |= uu < NU && wl4[k] == 0 && uu % (int)gridDim.x == (int)blockIdx.x;
             incl4[k] = wave_scan_i32(wl4[k]);
             P += __builtin_amdgcn_readlane(incl4[k], 63);
+        }
+    }
+    if (__ballot(empties)) {                               // rare: look again, one unit at a time
+        for (int uu = blockIdx.x; uu < NU; uu += gridDim.x) {
+            const UnitItems it = unit_items(a, uu);
+            if (it.nq + it.nr == 0) zero_fill(uu);
         }
     }
     QT_MARK(t_sum);
@@ -194,9 +211,9 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
         long running = 0;
         for (int base = 0; base < NU && up < 0; base += 256) {
             if (!small) {
+                lengths4(base, Tl, Rl);
 #pragma unroll
                 for (int k = 0; k < 4; k++) {
-                    lengths_of(base + 64 * k + lane, Tl[k], Rl[k]);
                     wl4[k] = weight_of(Tl[k], Rl[k]);
                     incl4[k] = wave_scan_i32(wl4[k]);
                 }
