@@ -86,7 +86,9 @@ def main():
     for i in range(ncopy):
         inp = W.make_inputs(w, dev, seed_offset=i)
         if shape is None:
-            shape = api.make_shape(w.B, w.Hq, w.Hkv, w.D, w.G, inp.Tcap, w.Rcap)
+            # ragged workloads draw new lengths for every copy: size the caches for the longest possible
+            tcap = w.tcap(w.L // w.G * w.G) if w.keep_range is not None else inp.Tcap
+            shape = api.make_shape(w.B, w.Hq, w.Hkv, w.D, w.G, tcap, w.Rcap)
         cache = api.Cache(shape, device=dev)
         n_max = int(inp.n_tok.max())
         e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
@@ -115,7 +117,8 @@ def main():
     t_build = time.time() - t_build
 
     q_len = copies[0]["n_tok"].cpu().tolist()
-    alg_bytes = W.algorithmic_bytes(w, q_len, [w.Rcap] * w.units)
+    bytes_of = [W.algorithmic_bytes(w, c["n_tok"].cpu().tolist(), [w.Rcap] * w.units) for c in copies]
+    alg_bytes = int(round(sum(bytes_of[(args.warmup + i) % ncopy] for i in range(args.steps)) / args.steps))
     append_bytes = 2 * w.units * w.D * 2 * 2               # read + write of the new K and V rows
 
     def step(i):
@@ -231,9 +234,14 @@ def main():
         samp_bytes = W.algorithmic_bytes(w, [q_len[u] for u in units], [w.Rcap] * nsamp)
         got = copies[0]["out"].view(w.B, w.Hkv, rep, w.D).reshape(w.units, rep, w.D)[sel].float().cpu().numpy()
         # copies[0] was last run in the event loop or the timed loop; its output is the step's result
-        err = float(np.max(np.abs(got - want.astype(np.float32))))
-        result["parity"] = {"max_abs_err_vs_oracle": err, "tolerance": 2e-3, "sample_units": nsamp,
-                            "ok": bool(err <= 2e-3)}
+        # tolerance: 2e-3, or one fp16 step of the oracle's value where that is larger (|o| >= 2)
+        wantf = want.astype(np.float32)
+        diff = np.abs(got - wantf)
+        step16 = np.spacing(np.abs(want).astype(np.float16)).astype(np.float32)
+        err = float(diff.max())
+        result["parity"] = {"max_abs_err_vs_oracle": err, "tolerance": "max(2e-3, one fp16 step of the value)",
+                            "max_abs_oracle_value": float(np.abs(wantf).max()), "sample_units": nsamp,
+                            "ok": bool(np.all(diff <= np.maximum(2e-3, step16)))}
         result["cpu_baseline"] = {
             "value": round(samp_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())),
             "kind": "oracle",

@@ -16,15 +16,16 @@ constexpr int kMinChunk = 512;     // smallest token chunk one workgroup of the 
 constexpr int kMaxRep = 8;         // most query heads per KV head
 constexpr int kMaxStreamWaves = 4096;  // most single-wave workgroups the decode kernel is launched with
 
-// Workspace layout of the single-launch decode kernel: per (unit, set of 4 query heads) a ticket counter
-// (zero between calls), then the split-K partials.
+// Workspace layout of the single-launch decode kernel: ticket counters (zero between calls) -- one per
+// (unit, set of 4 query heads) and one per partial slot for the sub-groups of 16 waves -- then the split-K
+// partials (slot = wave + 2 * unit, fewer than kMaxStreamWaves + 2 * units of them).
 __host__ __device__ inline size_t ws_units(const minikv_shape &s)
 {
     return (size_t)s.B * s.Hkv * ((s.Hq / s.Hkv + 3) / 4);
 }
 __host__ __device__ inline size_t ws_counter_bytes(const minikv_shape &s)
 {
-    return (ws_units(s) * sizeof(int) + 255) / 256 * 256;
+    return ((3 * ws_units(s) + kMaxStreamWaves) * sizeof(int) + 255) / 256 * 256;
 }
 
 // per-unit element counts

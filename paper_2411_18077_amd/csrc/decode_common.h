@@ -13,6 +13,7 @@ struct DecArgs {
     uint16_t *out;               // [B][Hq][D] fp16
     float *ws;                   // split-K partials (layout depends on the variant)
     int *cnt;                    // per-unit ticket counters of the single-launch kernel (zero between calls)
+    int *cnt1;                   // ticket counters of the sub-groups, indexed by the sub-group's first slot
     int first_slot;              // workgroups that fill the first wave slot of every SIMD
     float c1;                    // sm_scale * log2(e): scores are kept in the base-2 domain
     int Hq, Hkv, rep, Tcap, Rcap, chunk, nchunk;

@@ -198,6 +198,7 @@ int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache
     a.out = out;
     a.first_slot = 0;
     a.cnt = reinterpret_cast<int *>(workspace);
+    a.cnt1 = a.cnt + ws_units(s);
     a.ws = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + ws_counter_bytes(s));
     a.c1 = sm_scale * 1.44269504088896340736f;
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.rep = g.rep; a.Tcap = s.Tcap; a.Rcap = s.Rcap;

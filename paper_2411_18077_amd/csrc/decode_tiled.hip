@@ -676,42 +676,30 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
                 }
             }
         } else {
-            const int slot = w + 2 * up;
-#pragma unroll
-            for (int h = 0; h < kNH; h++) {
-                if (h < nheads) {
-                    float *pp = slot_ptr(a, slot, h);
-                    st_agent(pp + 4 + lane, oa[h]);
-                    st_agent(pp + 4 + lane + 64, ob[h]);
-                    if (lane == 0) { st_agent(pp, m[h]); st_agent(pp + 1, lsum[h]); }
-                }
-            }
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // all stores acknowledged ...
-            int old = 0;
-            if (lane == 0) old = atomicAdd(a.cnt + up, 1);           // ... before the ticket is taken
-            old = __builtin_amdgcn_readfirstlane(old);
-            QT_MARK(t_b1);
-            QT_ADD(7, t_b1 - t_b0);
-            if (old == expected - 1) {
-                // last partial of the unit to arrive: merge them all, write the output.  Lane s fetches
-                // (max, sum) of partial s, which gives every partial's weight; the output vectors (channels
-                // 2*lane, 2*lane+1 per lane) of up to 16 partials are requested in the same round trip.
-                // The group's slots are consecutive; all addresses are a wave-uniform base plus constants, so
-                // that the loads cost one instruction each (the merge runs alone on its SIMD at the end of
-                // the launch and is bound by instruction issue).
-                const char *const sbase = reinterpret_cast<const char *>(slot_ptr(a, wf + 2 * up, 0));
-                constexpr int kSlotB = kNH * kPartialStride * 4, kHeadB = kPartialStride * 4;
-                const int lane8 = lane * 8;
-                float M[kNH], L[kNH], Oa[kNH], Ob[kNH];
+            // Two-level merge.  The waves of the unit form sub-groups of 16 (by their place in the group);
+            // the last partial to arrive in a sub-group merges it -- the slots are consecutive, every
+            // address is a wave-uniform base plus constants, one round trip -- and, when the unit has more
+            // than one sub-group, writes the result over the sub-group's first slot and takes a ticket at
+            // the unit; the last sub-group to arrive merges those (slots 16 apart).  So a unit served by
+            // hundreds of waves still ends with two short merges, and the first level runs while other
+            // waves are still at work.
+            constexpr int kSlotB = kNH * kPartialStride * 4, kHeadB = kPartialStride * 4;
+            const int lane8 = lane * 8;
+            float M[kNH], L[kNH], Oa[kNH], Ob[kNH];
+            // merges `count` partials, `stride` slots apart from slot `first`, into (M, L, Oa, Ob): lane s
+            // fetches (max, sum) of partial s, which gives every partial's weight; the output vectors
+            // (channels 2*lane, 2*lane+1 per lane) of up to 16 partials are requested in the same round trip
+            auto merge = [&](int first, int stride, int count) {
+                const char *const sbase = reinterpret_cast<const char *>(slot_ptr(a, first, 0));
+                const size_t step = (size_t)stride * kSlotB;
 #pragma unroll
                 for (int h = 0; h < kNH; h++) { M[h] = -1e30f; L[h] = 0.f; Oa[h] = 0.f; Ob[h] = 0.f; }
                 constexpr int MB = 16;
 #pragma unroll 1
-                for (int base = 0; base < expected; base += MB) {
-                    const int cnt = min(MB, expected - base);
+                for (int base = 0; base < count; base += MB) {
+                    const int cnt = min(MB, count - base);
                     const bool has = lane < cnt;
-                    // lane s: (max, sum) of partial base+s for every head
-                    const char *const mine_p = sbase + (size_t)(base + (has ? lane : 0)) * kSlotB;
+                    const char *const mine_p = sbase + (size_t)(base + (has ? lane : 0)) * step;
                     float ms[kNH], ls[kNH], cm[kNH];
 #pragma unroll
                     for (int h = 0; h < kNH; h++) {
@@ -723,7 +711,7 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
                     float2 x[MB][kNH];
 #pragma unroll
                     for (int k = 0; k < MB; k++) {
-                        const char *const pk = sbase + (size_t)(base + min(k, cnt - 1)) * kSlotB;   // uniform
+                        const char *const pk = sbase + (size_t)(base + min(k, cnt - 1)) * step;   // uniform
 #pragma unroll
                         for (int h = 0; h < kNH; h++)
                             x[k][h] = ld_agent2(reinterpret_cast<const float *>(pk + h * kHeadB + 16 + lane8));
@@ -744,8 +732,6 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
                     wave_sum64x4(lw);
 #pragma unroll
                     for (int h = 0; h < kNH; h++) L[h] += lw[h];
-                    QT_MARK(t_m1);
-                    QT_ADD(20, t_m1 - t_b1);
 #pragma unroll
                     for (int k = 0; k < MB; k++)
 #pragma unroll
@@ -755,6 +741,8 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
                             Ob[h] += x[k][h].y * wl;
                         }
                 }
+            };
+            auto write_out = [&]() {
 #pragma unroll
                 for (int h = 0; h < kNH; h++) {
                     if (h >= nheads) continue;
@@ -762,7 +750,52 @@ __global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
                     const h2 r = {(_Float16)(Oa[h] * inv), (_Float16)(Ob[h] * inv)};
                     *reinterpret_cast<uint32_t *>(a.out + (size_t)(bq0 + h) * kD + 2 * lane) = as_u32(r);
                 }
-                if (lane == 0) a.cnt[up] = 0;              // ready for the next call
+            };
+            auto take_ticket = [&](int *counter) -> int {           // after this wave's stores are acknowledged
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                int old = 0;
+                if (lane == 0) old = atomicAdd(counter, 1);
+                return __builtin_amdgcn_readfirstlane(old);
+            };
+
+            const int me = w - wf, sg = me >> 4;
+            const int n1 = min(16, expected - 16 * sg), nsg = (expected + 15) >> 4;
+            const int slot1 = wf + 16 * sg + 2 * up;               // first slot of the sub-group
+            const int slot = w + 2 * up;
+#pragma unroll
+            for (int h = 0; h < kNH; h++) {
+                if (h < nheads) {
+                    float *pp = slot_ptr(a, slot, h);
+                    st_agent(pp + 4 + lane, oa[h]);
+                    st_agent(pp + 4 + lane + 64, ob[h]);
+                    if (lane == 0) { st_agent(pp, m[h]); st_agent(pp + 1, lsum[h]); }
+                }
+            }
+            const int old1 = take_ticket(a.cnt1 + slot1);
+            QT_MARK(t_b1);
+            QT_ADD(7, t_b1 - t_b0);
+            if (old1 == n1 - 1) {
+                merge(slot1, 1, n1);
+                if (lane == 0) a.cnt1[slot1] = 0;          // ready for the next call
+                if (nsg == 1) {
+                    write_out();
+                } else {
+#pragma unroll
+                    for (int h = 0; h < kNH; h++) {
+                        if (h < nheads) {
+                            float *pp = slot_ptr(a, slot1, h);
+                            st_agent(pp + 4 + 2 * lane, Oa[h]);
+                            st_agent(pp + 4 + 2 * lane + 1, Ob[h]);
+                            if (lane == 0) { st_agent(pp, M[h]); st_agent(pp + 1, L[h]); }
+                        }
+                    }
+                    const int old2 = take_ticket(a.cnt + up);
+                    if (old2 == nsg - 1) {
+                        merge(wf + 2 * up, 16, nsg);
+                        write_out();
+                        if (lane == 0) a.cnt[up] = 0;
+                    }
+                }
                 QT_MARK(t_b2);
                 QT_ADD(21, t_b2 - t_b1);
                 QT_ADD(8, t_b2 - t_b1);
