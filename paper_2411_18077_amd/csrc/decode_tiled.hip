@@ -107,8 +107,11 @@ extern "C" int minikv_debug_qtl(long long *host, int n)
 #define QT_MARK(var) do {} while (0)
 #endif
 
+// Two waves per SIMD, except for G = 16, whose per-lane share of the K scale / zero rows and of q*Ks does not
+// fit 256 registers: one wave per SIMD with the full register file runs 1.6x faster there than two that
+// spill (the pass loop is bound by instruction issue, which one wave nearly saturates).
 template <int G, bool LO>
-__global__ __launch_bounds__(64, 2) void decode_stream_kernel(DecArgs a)
+__global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecArgs a)
 {
     // K side: a K group spans G/2 token-lanes = BGK blocks of 4 lanes.  Block j of a group supplies the
     // A operand (4 heads x 4 channels of q*Ks) of k-steps j, j+BGK, ...; the matrix instruction
