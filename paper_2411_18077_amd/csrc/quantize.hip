@@ -76,6 +76,30 @@ __device__ inline void load_rows(uint16_t *tile, const uint16_t *src, const Quan
     }
 }
 
+typedef _Float16 qh2 __attribute__((ext_vector_type(2)));
+__device__ inline qh2 as_qh2(uint32_t u) { return __builtin_bit_cast(qh2, u); }
+__device__ inline qh2 pk_min(qh2 a, qh2 b) { return __builtin_elementwise_min(a, b); }
+__device__ inline qh2 pk_max(qh2 a, qh2 b) { return __builtin_elementwise_max(a, b); }
+
+// code of x as a float 0..3 (round half to even, clamped): every operation a separately rounded binary32 one
+__device__ inline float quant_codef(float x, float2 zi)
+{
+    const float d = x - zi.x;
+    const float u = d * zi.y;
+    return __builtin_amdgcn_fmed3f(rintf(u), 0.0f, 3.0f);
+}
+// Sixteen codes -> one word with code k at bit 16*(k%2) + 2*(k/2): the two half-words are summed as exact
+// binary32 numbers (code * 4^j < 2^16), one fused multiply-add per code, and converted once.
+struct WordAcc {
+    float lo = 0.f, hi = 0.f;
+    __device__ inline void add(int k, float code)             // k: compile-time position 0..15
+    {
+        const float wgt = (float)(1 << (2 * (k >> 1)));
+        if (k & 1) hi = __builtin_fmaf(code, wgt, hi); else lo = __builtin_fmaf(code, wgt, lo);
+    }
+    __device__ inline uint32_t word() const { return (uint32_t)lo | ((uint32_t)hi << 16); }
+};
+
 template <int G>
 __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
 {
@@ -84,8 +108,7 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
     constexpr int NPAR = (BT / G) * kD > BT * NCG ? (BT / G) * kD : BT * NCG;
 
     __shared__ __attribute__((aligned(16))) uint16_t tile[BT * kRow];
-    __shared__ float p_inv[NPAR];
-    __shared__ float p_zero[NPAR];
+    __shared__ __attribute__((aligned(16))) float2 par[NPAR];      // (zero, 1/scale) of every group
 
     const int u = blockIdx.y;
     const int tid = threadIdx.x;
@@ -96,27 +119,34 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
     const int nt = (n - i0 < BT) ? n - i0 : BT;        // multiple of G
     const int t0 = q0 + i0;                            // first destination token, multiple of G
 
-    // ---------------- K: groups of G tokens per channel
+    // ---------------- K: groups of G tokens per channel.  Statistics: one thread per (group, channel pair),
+    // packed fp16 min / max (exact) down the G tokens.
     load_rows<G>(tile, a.K, a, u, i0, nt);
     __syncthreads();
-    for (int gi = tid; gi < (nt / G) * kD; gi += 256) {
-        const int g = gi / kD, c = gi % kD;
-        float mn = INFINITY, mx = -INFINITY;
-        for (int i = g * G; i < (g + 1) * G; i++) {
-            float x = h2f(tile[i * kRow + c]);
-            mn = fminf(mn, x);
-            mx = fmaxf(mx, x);
+    for (int gi = tid; gi < (nt / G) * (kD / 2); gi += 256) {
+        const int g = gi / (kD / 2), cp = gi % (kD / 2);
+        const uint32_t *col = reinterpret_cast<const uint32_t *>(tile + g * G * kRow) + cp;
+        qh2 mn = as_qh2(col[0]), mx = mn;
+#pragma unroll 8
+        for (int i = 1; i < G; i++) {
+            const qh2 x = as_qh2(col[i * (kRow / 2)]);
+            mn = pk_min(mn, x);
+            mx = pk_max(mx, x);
         }
-        uint16_t sh, zh; float inv, zf;
-        group_params(mn, mx, sh, zh, inv, zf);
-        const size_t o = ((size_t)u * (a.Tcap / G) + (size_t)(t0 / G + g)) * kD + k_meta_pos(G, c);
-        a.Ks[o] = sh;
-        a.Kz[o] = zh;
-        p_inv[gi] = inv;
-        p_zero[gi] = zf;
+#pragma unroll
+        for (int e = 0; e < 2; e++) {
+            const int c = 2 * cp + e;
+            uint16_t sh, zh; float inv, zf;
+            group_params((float)mn[e], (float)mx[e], sh, zh, inv, zf);
+            const size_t o = ((size_t)u * (a.Tcap / G) + (size_t)(t0 / G + g)) * kD + k_meta_pos(G, c);
+            a.Ks[o] = sh;
+            a.Kz[o] = zh;
+            par[g * kD + c] = float2{zf, inv};
+        }
     }
     __syncthreads();
     {
+        // one thread per (token, word): the word's 16 channels are contiguous in the tile row and in par
         uint32_t *Kc = a.Kc + (size_t)u * kc_words(a.Tcap);
         const int npair = nt / 2;
         for (int wi = tid; wi < nt * 8; wi += 256) {
@@ -125,53 +155,70 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
             const int ch = wi / (4 * npair);           // 0..3 = 2*(token parity) + (word half)
             const int i = 2 * pr + (ch >> 1);
             const int w = (ch & 1) * 4 + wq;
-            const int g = i / G;
-            uint32_t word = 0;
+            const uint4 *xs = reinterpret_cast<const uint4 *>(tile + i * kRow + 16 * w);
+            const float4 *ps = reinterpret_cast<const float4 *>(par + (i / G) * kD + 16 * w);
+            WordAcc acc;
 #pragma unroll
-            for (int k = 0; k < 16; k++) {
-                const int c = 16 * w + k;
-                float x = h2f(tile[i * kRow + c]);
-                word |= quant_code(x, p_zero[g * kD + c], p_inv[g * kD + c]) << k_bit(c);
+            for (int h = 0; h < 2; h++) {
+                const uint4 x4 = xs[h];
+                const uint32_t xw[4] = {x4.x, x4.y, x4.z, x4.w};
+#pragma unroll
+                for (int k2 = 0; k2 < 4; k2++) {
+                    const qh2 x = as_qh2(xw[k2]);
+                    const float4 p = ps[4 * h + k2];   // (zero, inv) of channels 8h + 2k2, 8h + 2k2 + 1
+                    acc.add(8 * h + 2 * k2, quant_codef((float)x[0], float2{p.x, p.y}));
+                    acc.add(8 * h + 2 * k2 + 1, quant_codef((float)x[1], float2{p.z, p.w}));
+                }
             }
-            Kc[k_word_index(t0 + i, w)] = word;
+            Kc[k_word_index(t0 + i, w)] = acc.word();
         }
     }
     __syncthreads();
 
-    // ---------------- V: groups of G channels per token
+    // ---------------- V: groups of G channels per token.  Statistics: one thread per (token, channel group),
+    // the G values read 8 at a time.
     load_rows<G>(tile, a.V, a, u, i0, nt);
     __syncthreads();
     for (int gi = tid; gi < nt * NCG; gi += 256) {
         const int i = gi / NCG, cg = gi % NCG;
-        float mn = INFINITY, mx = -INFINITY;
-        for (int c = cg * G; c < (cg + 1) * G; c++) {
-            float x = h2f(tile[i * kRow + c]);
-            mn = fminf(mn, x);
-            mx = fmaxf(mx, x);
+        const uint4 *xs = reinterpret_cast<const uint4 *>(tile + i * kRow + cg * G);
+        qh2 mn, mx;
+#pragma unroll
+        for (int k = 0; k < G / 8; k++) {
+            const uint4 x4 = xs[k];
+            const qh2 x0 = as_qh2(x4.x), x1 = as_qh2(x4.y), x2 = as_qh2(x4.z), x3 = as_qh2(x4.w);
+            const qh2 lo = pk_min(pk_min(x0, x1), pk_min(x2, x3)), hi = pk_max(pk_max(x0, x1), pk_max(x2, x3));
+            mn = k ? pk_min(mn, lo) : lo;
+            mx = k ? pk_max(mx, hi) : hi;
         }
+        const float mnf = fminf((float)mn[0], (float)mn[1]), mxf = fmaxf((float)mx[0], (float)mx[1]);
         uint16_t sh, zh; float inv, zf;
-        group_params(mn, mx, sh, zh, inv, zf);
+        group_params(mnf, mxf, sh, zh, inv, zf);
         const size_t o = ((size_t)u * a.Tcap + (size_t)(t0 + i)) * NCG + cg;
         a.Vs[o] = sh;
         a.Vz[o] = zh;
-        p_inv[gi] = inv;
-        p_zero[gi] = zf;
+        par[gi] = float2{zf, inv};
     }
     __syncthreads();
     {
+        // one thread per (block of 16 tokens, channel pair): two words
         uint32_t *Vc = a.Vc + (size_t)u * vc_words(a.Tcap);
         const int nb = nt / 16;
-        for (int wi = tid; wi < nb * kD; wi += 256) {
-            const int bl = wi % nb, c = wi / nb;
-            const int cg = c / G;
-            uint32_t word = 0;
+        for (int wi = tid; wi < nb * (kD / 2); wi += 256) {
+            const int bl = wi % nb, cp = wi / nb;
+            const int cg = (2 * cp) / G;
+            const uint32_t *col = reinterpret_cast<const uint32_t *>(tile + 16 * bl * kRow) + cp;
+            const float2 *ps = par + (16 * bl) * NCG + cg;
+            WordAcc acc0, acc1;
 #pragma unroll
             for (int p = 0; p < 16; p++) {
-                const int i = 16 * bl + p;
-                float x = h2f(tile[i * kRow + c]);
-                word |= quant_code(x, p_zero[i * NCG + cg], p_inv[i * NCG + cg]) << v_bit(p);
+                const qh2 x = as_qh2(col[p * (kRow / 2)]);
+                const float2 zi = ps[p * NCG];
+                acc0.add(p, quant_codef((float)x[0], zi));
+                acc1.add(p, quant_codef((float)x[1], zi));
             }
-            Vc[v_word_index(t0 / 16 + bl, c)] = word;
+            Vc[v_word_index(t0 / 16 + bl, 2 * cp)] = acc0.word();
+            Vc[v_word_index(t0 / 16 + bl, 2 * cp + 1)] = acc1.word();
         }
     }
 }
