@@ -110,9 +110,15 @@ extern "C" int minikv_debug_qtl(long long *host, int n)
 // Two waves per SIMD, except for G = 16, whose per-lane share of the K scale / zero rows and of q*Ks does not
 // fit 256 registers: one wave per SIMD with the full register file runs 1.6x faster there than two that
 // spill (the pass loop is bound by instruction issue, which one wave nearly saturates).
-template <int G, bool LO>
+//
+// PAIRED (units with at most two query heads, i.e. multi-head attention): the four rows of the K-phase
+// A operand are (head 0 hi, head 0 lo, head 1 hi, head 1 lo) instead of four heads, so one matrix
+// instruction does the work of the hi and the lo one, and the two result rows of a head are added afterwards.
+template <int G, bool LO, bool PAIRED>
 __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecArgs a)
 {
+    static_assert(!PAIRED || LO, "the paired rows are the hi and lo parts");
+    constexpr int NHQ = PAIRED ? 2 : kNH;                  // heads the quantized passes work on
     // K side: a K group spans G/2 token-lanes = BGK blocks of 4 lanes.  Block j of a group supplies the
     // A operand (4 heads x 4 channels of q*Ks) of k-steps j, j+BGK, ...; the matrix instruction
     // broadcasts it to the other blocks of the group (cbsz = log2 BGK, abid = j).
@@ -477,7 +483,8 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             for (int i = 0; i < NKR; i++) {
                 const int c = 4 * (bbk + BGK * i);
                 uint2 bits = {0u, 0u};
-                if (row < nheads && j0 < j1) bits = *reinterpret_cast<const uint2 *>(a.q + (size_t)(bq0 + row) * kD + c);
+                const int hq = PAIRED ? row >> 1 : row;    // the head whose A rows this lane supplies
+                if (hq < nheads && j0 < j1) bits = *reinterpret_cast<const uint2 *>(a.q + (size_t)(bq0 + hq) * kD + c);
                 qraw[i][0] = as_h2(bits.x);
                 qraw[i][1] = as_h2(bits.y);
 #pragma unroll
@@ -485,7 +492,7 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                     qscl[i][ep] = qraw[i][ep] * (_Float16)fld_scale(((c + 2 * ep) & 15) >> 1);
             }
 
-            float s0[kNH], s1[kNH];                        // scores of the lane's two tokens
+            float s0[kNH], s1[kNH];                        // scores of the lane's two tokens (NHQ heads)
 
             // ---------------- K phase: scores of tokens 2*lane, 2*lane+1 for the 4 heads
             auto k_phase = [&](const KD &d, int tp) {
@@ -503,8 +510,13 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                         if constexpr (LO) lo[ep] = __builtin_elementwise_fma(qscl[i][ep], ks2, -hi[ep]);
                         qz = __builtin_amdgcn_fdot2(qraw[i][ep], kz2, qz, false);
                     }
-                    a_hi[i] = h4{hi[0][0], hi[0][1], hi[1][0], hi[1][1]};
-                    if constexpr (LO) a_lo[i] = h4{lo[0][0], lo[0][1], lo[1][0], lo[1][1]};
+                    if constexpr (PAIRED) {                 // odd rows carry the lo part
+                        const h2 u0 = (row & 1) ? lo[0] : hi[0], u1 = (row & 1) ? lo[1] : hi[1];
+                        a_hi[i] = h4{u0[0], u0[1], u1[0], u1[1]};
+                    } else {
+                        a_hi[i] = h4{hi[0][0], hi[0][1], hi[1][0], hi[1][1]};
+                        if constexpr (LO) a_lo[i] = h4{lo[0][0], lo[0][1], lo[1][0], lo[1][1]};
+                    }
                 }
                 // sum the partial qz of the BGK blocks of the group (same row, lanes 4 apart)
                 if constexpr (BGK == 2) qz += __shfl_xor(qz, 4);
@@ -525,15 +537,24 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                         const h4 b0 = {x00[0], x00[1], x01[0], x01[1]};
                         const h4 b1 = {x10[0], x10[1], x11[0], x11[1]};
                         mfma_k<CBK>(acc0, acc1, a_hi[s / BGK], b0, b1, s % BGK);
-                        if constexpr (LO) mfma_k<CBK>(acc0, acc1, a_lo[s / BGK], b0, b1, s % BGK);
+                        if constexpr (LO && !PAIRED) mfma_k<CBK>(acc0, acc1, a_lo[s / BGK], b0, b1, s % BGK);
                     }
                 }
-                const float zz[kNH] = {quad_bcast<0>(qz) * a.c1, quad_bcast<1>(qz) * a.c1,
-                                       quad_bcast<2>(qz) * a.c1, quad_bcast<3>(qz) * a.c1};
+                if constexpr (PAIRED) {
+                    const float zz[2] = {quad_bcast<0>(qz) * a.c1, quad_bcast<2>(qz) * a.c1};
 #pragma unroll
-                for (int h = 0; h < kNH; h++) {
-                    s0[h] = valid ? acc0[h] * kscale + zz[h] : -INFINITY;
-                    s1[h] = valid ? acc1[h] * kscale + zz[h] : -INFINITY;
+                    for (int h = 0; h < 2; h++) {
+                        s0[h] = valid ? (acc0[2 * h] + acc0[2 * h + 1]) * kscale + zz[h] : -INFINITY;
+                        s1[h] = valid ? (acc1[2 * h] + acc1[2 * h + 1]) * kscale + zz[h] : -INFINITY;
+                    }
+                } else {
+                    const float zz[kNH] = {quad_bcast<0>(qz) * a.c1, quad_bcast<1>(qz) * a.c1,
+                                           quad_bcast<2>(qz) * a.c1, quad_bcast<3>(qz) * a.c1};
+#pragma unroll
+                    for (int h = 0; h < kNH; h++) {
+                        s0[h] = valid ? acc0[h] * kscale + zz[h] : -INFINITY;
+                        s1[h] = valid ? acc1[h] * kscale + zz[h] : -INFINITY;
+                    }
                 }
             };
 
@@ -543,16 +564,16 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                 float mn[kNH];
                 bool grow = false;
 #pragma unroll
-                for (int h = 0; h < kNH; h++) mn[h] = fmaxf(s0[h], s1[h]);
-                wave_max64x4(mn);
+                for (int h = 0; h < NHQ; h++) mn[h] = fmaxf(s0[h], s1[h]);
+                if constexpr (PAIRED) wave_max64x2(mn); else wave_max64x4(mn);
 #pragma unroll
-                for (int h = 0; h < kNH; h++) {
+                for (int h = 0; h < NHQ; h++) {
                     mn[h] = fmaxf(m[h], mn[h]);
                     grow |= mn[h] > m[h];
                 }
                 if (grow) {                                // wave-uniform
 #pragma unroll
-                    for (int h = 0; h < kNH; h++) {
+                    for (int h = 0; h < NHQ; h++) {
                         const float sc = fast_exp2(m[h] - mn[h]);
                         l_lane[h] *= sc;
                         O0[h] *= sc;
@@ -575,7 +596,7 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                         vzp[g] = as_h2(valid ? zv : 0u);
                     }
 #pragma unroll
-                    for (int h = 0; h < kNH; h++) {
+                    for (int h = 0; h < NHQ; h++) {
                         const float mo = m[h] - lg;
                         const float p0 = fast_exp2(s0[h] - mo), p1 = fast_exp2(s1[h] - mo);   // masked: 0
                         l_lane[h] += p0 + p1;
@@ -816,14 +837,14 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
 #endif
 }
 
-template <int G, bool LO>
+template <int G, bool LO, bool PAIRED>
 static int launch_stream(DecArgs a, hipStream_t st)
 {
     constexpr int NCG = kD / G;
     constexpr size_t q_bytes = (size_t)NCG * kPsG * 2;
     constexpr size_t r_bytes = (size_t)kNH * kD * 2 + (size_t)64 * kKRowH * 2;
     constexpr size_t lds_bytes = q_bytes > r_bytes ? q_bytes : r_bytes;
-    auto kern = decode_stream_kernel<G, LO>;
+    auto kern = decode_stream_kernel<G, LO, PAIRED>;
     static int resident = 0;                               // single-wave workgroups the device holds at once
     if (resident == 0) {
         int dev = 0, cus = 0, per_cu = 0;
@@ -846,14 +867,14 @@ static int launch_stream(DecArgs a, hipStream_t st)
     return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
 }
 
-template <bool LO>
+template <bool LO, bool PAIRED>
 static int launch_stream_g(const DecArgs &a, int G, hipStream_t st)
 {
     switch (G) {
-    case 16: return launch_stream<16, LO>(a, st);
-    case 32: return launch_stream<32, LO>(a, st);
-    case 64: return launch_stream<64, LO>(a, st);
-    case 128: return launch_stream<128, LO>(a, st);
+    case 16: return launch_stream<16, LO, PAIRED>(a, st);
+    case 32: return launch_stream<32, LO, PAIRED>(a, st);
+    case 64: return launch_stream<64, LO, PAIRED>(a, st);
+    case 128: return launch_stream<128, LO, PAIRED>(a, st);
     }
     return MINIKV_EUNSUPPORTED;
 }
@@ -862,8 +883,8 @@ int launch_decode_tiled(const DecArgs &a, int G, int units, int variant, hipStre
 {
     (void)units;
     switch (variant) {
-    case 3: return launch_stream_g<true>(a, G, st);
-    case 4: return launch_stream_g<false>(a, G, st);
+    case 3: return a.rep <= 2 ? launch_stream_g<true, true>(a, G, st) : launch_stream_g<true, false>(a, G, st);
+    case 4: return launch_stream_g<false, false>(a, G, st);
     }
     return MINIKV_EINVAL;
 }

@@ -69,6 +69,23 @@ __device__ inline void wave_max64x4(float v[4])
     asm volatile("s_nop 1\n" MINIKV_WAVE64("max") : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]));
     for (int i = 0; i < 4; i++) v[i] = lane63(v[i]);
 }
+// the same for two values (the wait states between dependent DPP steps are filled with s_nop)
+#define MINIKV_DPP2(op, ctrl)                                                     \
+    "v_" op "_f32_dpp %0, %0, %0 " ctrl " bank_mask:0xf\n"                        \
+    "v_" op "_f32_dpp %1, %1, %1 " ctrl " bank_mask:0xf\n"                        \
+    "s_nop 0\n"
+#define MINIKV_WAVE64X2(op)                                                       \
+    MINIKV_DPP2(op, "quad_perm:[1,0,3,2] row_mask:0xf")                           \
+    MINIKV_DPP2(op, "quad_perm:[2,3,0,1] row_mask:0xf")                           \
+    MINIKV_DPP2(op, "row_half_mirror row_mask:0xf")                               \
+    MINIKV_DPP2(op, "row_mirror row_mask:0xf")                                    \
+    MINIKV_DPP2(op, "row_bcast:15 row_mask:0xa")                                  \
+    MINIKV_DPP2(op, "row_bcast:31 row_mask:0xc")
+__device__ inline void wave_max64x2(float v[2])
+{
+    asm volatile("s_nop 1\n" MINIKV_WAVE64X2("max") : "+v"(v[0]), "+v"(v[1]));
+    for (int i = 0; i < 2; i++) v[i] = lane63(v[i]);
+}
 // v[i] <- sum of v[i] over the wave (wave-uniform)
 __device__ inline void wave_sum64x4(float v[4])
 {
