@@ -409,3 +409,75 @@ int minikv_decode_attn_ref(const ref_shape *s, const uint16_t *q, const ref_cach
     }
     return fail ? -1 : 0;
 }
+
+/* ---------------------------------------------------------------------------------------------------
+ * Token selection: Section 3.1.2 and Algorithm 1 line 3 (heavy hitters from the cumulative attention
+ * score, plus the recent window).
+ * ------------------------------------------------------------------------------------------------- */
+typedef struct {
+    float score;
+    int32_t pos;
+} scored_pos;
+
+/* larger score first; of equal scores the earlier position first */
+static int by_score_then_pos(const void *a, const void *b)
+{
+    const scored_pos *x = (const scored_pos *)a, *y = (const scored_pos *)b;
+    if (x->score > y->score) return -1;
+    if (x->score < y->score) return 1;
+    return (x->pos > y->pos) - (x->pos < y->pos);
+}
+
+static int by_pos(const void *a, const void *b)
+{
+    const scored_pos *x = (const scored_pos *)a, *y = (const scored_pos *)b;
+    return (x->pos > y->pos) - (x->pos < y->pos);
+}
+
+int kv_select_hh_rw_ref(int32_t units, int32_t rep, int64_t L, const float *A_cumul,
+                        const int32_t *n_hh, const int32_t *n_rw, int32_t *idx, int64_t idx_stride,
+                        int32_t *n_tok)
+{
+    if (units < 0 || rep < 1 || L < 0 || L > INT32_MAX || idx_stride < 0) return -1;
+    if (units > 0 && (!A_cumul || !n_hh || !n_rw || !idx || !n_tok)) return -1;
+    scored_pos *cand = (scored_pos *)malloc(sizeof(scored_pos) * (size_t)(L > 0 ? L : 1));
+    if (!cand) return -1;
+    for (int32_t u = 0; u < units; ++u) {
+        const int64_t rw = n_rw[u], hh = n_hh[u];
+        if (rw < 0 || hh < 0 || rw > L || hh > L - rw || hh + rw > idx_stride) {
+            n_tok[u] = 0;
+            continue;
+        }
+        const int64_t n_cand = L - rw;                 /* the recent window is kept whatever its score */
+        for (int64_t i = 0; i < n_cand; ++i) {
+            float s = A_cumul[((size_t)u * (size_t)rep) * (size_t)L + (size_t)i];
+            for (int32_t h = 1; h < rep; ++h)
+                s = s + A_cumul[((size_t)u * (size_t)rep + (size_t)h) * (size_t)L + (size_t)i];
+            cand[i].score = s;
+            cand[i].pos = (int32_t)i;
+        }
+        qsort(cand, (size_t)n_cand, sizeof(scored_pos), by_score_then_pos);
+        qsort(cand, (size_t)hh, sizeof(scored_pos), by_pos);      /* the heavy hitters, by position */
+        int32_t *row = idx + (size_t)u * (size_t)idx_stride;
+        for (int64_t i = 0; i < hh; ++i) row[i] = cand[i].pos;
+        for (int64_t i = 0; i < rw; ++i) row[hh + i] = (int32_t)(n_cand + i);
+        n_tok[u] = (int32_t)(hh + rw);
+    }
+    free(cand);
+    return 0;
+}
+
+/* Section 3.1.3 (pyramid-like allocation) and the appendix paragraph on its details. */
+int kv_pyramid_budget_ref(int32_t n_layers, double x, int32_t d, int32_t bottom_heavy, double *budget)
+{
+    if (n_layers < 1 || d < 1 || !(x >= 0.0) || !budget) return -1;
+    if (n_layers == 1) {
+        budget[0] = x;
+        return 0;
+    }
+    const double small = x / (double)d, large = 2.0 * x - x / (double)d;
+    const double first = bottom_heavy ? large : small, last = bottom_heavy ? small : large;
+    for (int32_t l = 0; l < n_layers; ++l)
+        budget[l] = first + (last - first) * (double)l / (double)(n_layers - 1);
+    return 0;
+}

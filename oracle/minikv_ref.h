@@ -25,8 +25,10 @@
  * Pins (tests/ with -m "not gpu"): round-trip half-step bound, code 0/3 presence, lossless lattice,
  * fp64 arg-min brute force with explicit ties, hand-derived packed words, Appendix I size arithmetic,
  * fp64 exact attention on a separately dequantized cache, softmax rows summing to 1, T=0 and r=0
- * special cases, uniform-weight case, GQA == replicated MHA, unit permutation.  No function here is
- * "parity unpinned".
+ * special cases, uniform-weight case, GQA == replicated MHA, unit permutation; for the token selection:
+ * a library sort with explicit tie keys, monotone / constant score closed forms, exhaustive tiny cases,
+ * boundary budgets, pre-summed heads; for the pyramid budget: mean, end points, linearity.  No function
+ * here is "parity unpinned".
  */
 #ifndef MINIKV_REF_H
 #define MINIKV_REF_H
@@ -82,6 +84,25 @@ int kv_flush_residual_ref(const ref_shape *s, ref_cache *c);
  * probs [B*Hq][Tcap+Rcap] softmax weights, quantized tokens first then residual (may be NULL). */
 int minikv_decode_attn_ref(const ref_shape *s, const uint16_t *q, const ref_cache *c, float sm_scale,
                            uint16_t *out_f16, double *out_f64, double *probs);
+
+/* Section 3.1.2 (heavy hitters and recent window) + Algorithm 1 line 3.  For every unit u the score of
+ * prompt token i is the binary32 sum, query heads in ascending order, of the rep rows
+ * A_cumul[(u*rep + h)*L + i].  Kept tokens: the n_rw[u] last prompt tokens (recent window) and, of the
+ * L - n_rw[u] others, the n_hh[u] with the largest score; of equal scores the earlier position wins.
+ * idx[u*idx_stride + 0..n_tok[u]) receives the kept positions in ascending order, n_tok[u] = n_hh[u] +
+ * n_rw[u].  A unit whose budgets are out of range (negative, n_rw > L, n_hh > L - n_rw, or
+ * n_hh + n_rw > idx_stride) gets n_tok[u] = 0 and its idx row is left alone.  Scores must not be NaN.
+ * Returns 0, or -1 on bad arguments. */
+int kv_select_hh_rw_ref(int32_t units, int32_t rep, int64_t L, const float *A_cumul,
+                        const int32_t *n_hh, const int32_t *n_rw, int32_t *idx, int64_t idx_stride,
+                        int32_t *n_tok);
+
+/* Section 3.1.3, pyramid-like allocation, and its appendix paragraph: heavy-hitter budget of each of
+ * n_layers layers for an average budget x and pyramid depth d: one end layer gets x/d, the other
+ * 2x - x/d, the layers between are linearly interpolated.  bottom_heavy != 0 gives layer 0 the large end
+ * (what the prose and the cited source say), 0 the small end (the appendix formula as printed).
+ * n_layers == 1 gives x.  Returns 0, or -1 on bad arguments (n_layers < 1, d < 1, x < 0). */
+int kv_pyramid_budget_ref(int32_t n_layers, double x, int32_t d, int32_t bottom_heavy, double *budget);
 
 /* Layout-free views for tests: codes[unit][t][ch] (0..3) and the dequantized values code*s+z. */
 int ref_unpack_codes(const ref_shape *s, const ref_cache *c, int unit, uint8_t *Kcodes, uint8_t *Vcodes);

@@ -37,7 +37,7 @@ def lib():
         _lib.ref_group_bytes.argtypes = [C.c_int]
         for name in ("ref_check_shape", "kv_quantize_pack_ref", "kv_append_residual_ref",
                      "kv_flush_residual_ref", "minikv_decode_attn_ref", "ref_unpack_codes", "ref_dequant",
-                     "ref_k_meta_pos"):
+                     "ref_k_meta_pos", "kv_select_hh_rw_ref", "kv_pyramid_budget_ref"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -127,6 +127,35 @@ def decode_attn(cache: RefCache, q, sm_scale, want_f64=False, want_probs=False):
     if rc:
         raise RuntimeError("minikv_decode_attn_ref failed: %d" % rc)
     return out16, out64, probs
+
+
+def select_hh_rw(A_cumul, n_hh, n_rw, rep=1, idx_stride=None):
+    """A_cumul float32 [U*rep, L]; n_hh, n_rw int32 [U] -> (idx int32 [U, idx_stride] filled with -1 beyond
+    n_tok, n_tok int32 [U])."""
+    A = np.ascontiguousarray(A_cumul)
+    assert A.dtype == np.float32 and A.ndim == 2 and A.shape[0] % rep == 0
+    U, L = A.shape[0] // rep, A.shape[1]
+    n_hh = np.ascontiguousarray(n_hh, np.int32)
+    n_rw = np.ascontiguousarray(n_rw, np.int32)
+    assert n_hh.shape == (U,) and n_rw.shape == (U,)
+    if idx_stride is None:
+        idx_stride = L
+    idx = np.full((U, idx_stride), -1, np.int32)
+    n_tok = np.full(U, -1, np.int32)
+    rc = lib().kv_select_hh_rw_ref(C.c_int32(U), C.c_int32(rep), C.c_int64(L), _p(A), _p(n_hh), _p(n_rw),
+                                   _p(idx), C.c_int64(idx_stride), _p(n_tok))
+    if rc:
+        raise RuntimeError("kv_select_hh_rw_ref failed: %d" % rc)
+    return idx, n_tok
+
+
+def pyramid_budget(n_layers, x, d=7, bottom_heavy=True):
+    out = np.zeros(max(n_layers, 1), np.float64)
+    rc = lib().kv_pyramid_budget_ref(C.c_int32(n_layers), C.c_double(x), C.c_int32(d),
+                                     C.c_int32(1 if bottom_heavy else 0), _p(out))
+    if rc:
+        raise RuntimeError("kv_pyramid_budget_ref failed: %d" % rc)
+    return out
 
 
 def unpack_codes(cache: RefCache, unit):

@@ -151,6 +151,40 @@ def make_inputs(w: Workload, device="cpu", seed_offset=0, unit_chunk=None):
     return Inputs(w, K, V, idx, n_tok.to(dev), q, Rk, Rv, Tcap, out_ch)
 
 
+def make_scores(rows, L, seed, device="cpu", kind="attention"):
+    """fp32 [rows, L] stand-ins for the cumulative attention score of each prompt token (the column sums
+    of a causal attention map, one row per query head).  Real maps need a model; these have their shape:
+    "attention": heavy-tailed positive values (a Pareto draw with tail index 1.2) times the share of query
+                 rows that can see the column, (L - i) / L, with a few sink tokens at the start made large;
+    "ties":      values on a grid of 8 levels, so most comparisons are between equal scores;
+    "signed":    N(0,1) draws, negative values and both zeros included (not attention-like; exercises the
+                 ordering of arbitrary finite floats).
+    """
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    if kind == "attention":
+        u = torch.rand(rows, L, generator=gen, device=dev, dtype=torch.float32).clamp_(min=1e-7)
+        visible = (L - torch.arange(L, device=dev, dtype=torch.float32)) / float(L)
+        a = (u.pow(-1.0 / 1.2) - 1.0 + 0.05) * visible
+        a[:, : min(4, L)] *= 50.0
+        return a.contiguous()
+    if kind == "ties":
+        return (torch.randint(0, 8, (rows, L), generator=gen, device=dev).to(torch.float32) / 8.0).contiguous()
+    if kind == "signed":
+        a = torch.randn(rows, L, generator=gen, device=dev, dtype=torch.float32)
+        a[:, ::7] = 0.0
+        a[:, 3::14] = -0.0
+        return a.contiguous()
+    raise ValueError(kind)
+
+
+def selection_bytes(units, rep, L, n_tok):
+    """Bytes the token selection must move: rep fp32 score rows of L tokens in, the kept positions
+    (int32) and the three per-unit counts out/in."""
+    return units * rep * L * 4 + int(sum(int(t) for t in n_tok)) * 4 + units * 12
+
+
 def algorithmic_bytes(w: Workload, q_len, r_len):
     """Bytes one decode-attention step must move: per retained token 2*D/4 code bytes plus
     2*(D/G) fp16 (scale, zero) pairs for K and for V, i.e. 64 + 8*D/G bytes; per residual token
