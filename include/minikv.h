@@ -132,6 +132,37 @@ int minikv_decode_attn(const minikv_shape *shape, const minikv_f16 *q, const min
                        float sm_scale, minikv_f16 *out, void *workspace, size_t workspace_bytes,
                        void *stream);
 
+/* Section 3.1.2 (heavy hitters vs. recent window) / Algorithm 1 line 3: which prompt tokens a unit keeps.
+ * The score of prompt token i of unit u is the binary32 sum, query heads in ascending order, of the rep
+ * rows A_cumul[(u*rep + h)*L + i] (the cumulative attention score of Algorithm 1 line 2; under grouped-query
+ * attention the heads of a group share one kept set, so their scores are added).  Kept: the n_rw[u] last
+ * prompt tokens (the recent window) and, of the L - n_rw[u] others, the n_hh[u] with the largest score (the
+ * heavy hitters); of equal scores the earlier position is kept.  idx[u*idx_stride + 0..n_tok[u]) receives
+ * the kept positions in ascending order and n_tok[u] = n_hh[u] + n_rw[u]: exactly what kv_quantize_pack
+ * takes (which in addition wants n_tok[u] to be a multiple of G: choose the budgets accordingly).
+ *   units      number of (batch, KV head) units; rep = query heads per KV head (>= 1)
+ *   A_cumul    fp32 [units*rep][L], finite, no NaN                        (device, read)
+ *   n_hh, n_rw int32 [units]                                              (device, read)
+ *   idx        int32 [units][idx_stride]; n_tok int32 [units]             (device, written)
+ *   workspace  device scratch of at least kv_select_workspace_bytes(units, rep, L) bytes (0 when rep == 1:
+ *              NULL is then accepted); contents private, no initial state required.
+ * A unit whose budgets are out of range (negative, n_rw > L, n_hh > L - n_rw, n_hh + n_rw > idx_stride)
+ * gets n_tok[u] = 0 and its idx row is left alone.  L <= 2^30. */
+size_t kv_select_workspace_bytes(int32_t units, int32_t rep, int64_t L);
+int kv_select_hh_rw(int32_t units, int32_t rep, int64_t L, const float *A_cumul, const int32_t *n_hh,
+                    const int32_t *n_rw, int32_t *idx, int64_t idx_stride, int32_t *n_tok, void *workspace,
+                    size_t workspace_bytes, void *stream);
+
+/* Section 3.1.3 (pyramid-like allocation) and the appendix paragraph on its details.  HOST arithmetic, no
+ * device work: heavy-hitter budget of each of n_layers layers for an average budget x (tokens) and pyramid
+ * depth d (the paper uses 7): one end layer gets x/d, the other 2x - x/d, the layers between are linearly
+ * interpolated, so the mean stays x.  bottom_heavy != 0 gives layer 0 the large end (lower layers hold
+ * more, as the section's text and the cited source say); 0 gives layer 0 the small end (the appendix
+ * formula as printed).  n_layers == 1 gives x.
+ *   budget  double [n_layers]                                             (HOST, written)
+ * Returns MINIKV_EINVAL for n_layers < 1, d < 1, x < 0 or NaN, or a null pointer. */
+int kv_pyramid_budget(int32_t n_layers, double x, int32_t d, int32_t bottom_heavy, double *budget);
+
 /* Diagnostics: selects the kernel variant minikv_decode_attn launches (process-wide).
  *   0 = default (fastest verified), 1 = plain scalar-loop kernel kept for cross-checks,
  *   others as listed by minikv_strvariant().  Returns MINIKV_EINVAL for an unknown id. */

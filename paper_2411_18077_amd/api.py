@@ -65,6 +65,12 @@ def lib():
         l.minikv_decode_attn.restype = C.c_int
         l.minikv_decode_attn.argtypes = [C.POINTER(MinikvShape), P, C.POINTER(MinikvCache), C.c_float, P, P,
                                          C.c_size_t, P]
+        l.kv_select_workspace_bytes.restype = C.c_size_t
+        l.kv_select_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int64]
+        l.kv_select_hh_rw.restype = C.c_int
+        l.kv_select_hh_rw.argtypes = [C.c_int32, C.c_int32, C.c_int64, P, P, P, P, C.c_int64, P, P, C.c_size_t, P]
+        l.kv_pyramid_budget.restype = C.c_int
+        l.kv_pyramid_budget.argtypes = [C.c_int32, C.c_double, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
         _lib = l
     return _lib
 
@@ -144,6 +150,23 @@ def minikv_decode_attn(shape, q, cache, sm_scale, out, workspace=None, stream=No
     ws = cache.workspace if workspace is None else workspace
     _check(lib().minikv_decode_attn(C.byref(shape), _ptr(q), C.byref(cc), float(sm_scale), _ptr(out), _ptr(ws),
                                     ws.numel() * ws.element_size(), _stream(stream)), "minikv_decode_attn")
+
+
+def kv_select_workspace_bytes(units, rep, L):
+    return int(lib().kv_select_workspace_bytes(int(units), int(rep), int(L)))
+
+
+def kv_select_hh_rw(units, rep, L, A_cumul, n_hh, n_rw, idx, idx_stride, n_tok, workspace=None, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().kv_select_hh_rw(int(units), int(rep), int(L), _ptr(A_cumul), _ptr(n_hh), _ptr(n_rw), _ptr(idx),
+                                 int(idx_stride), _ptr(n_tok), _ptr(workspace), nbytes, _stream(stream)),
+           "kv_select_hh_rw")
+
+
+def kv_pyramid_budget(n_layers, x, d, bottom_heavy):
+    out = (C.c_double * max(int(n_layers), 1))()
+    _check(lib().kv_pyramid_budget(int(n_layers), float(x), int(d), int(bottom_heavy), out), "kv_pyramid_budget")
+    return list(out)[: int(n_layers)]
 
 
 def minikv_set_variant(v):

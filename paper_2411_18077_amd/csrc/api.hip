@@ -145,6 +145,37 @@ int minikv_decode_attn(const minikv_shape *s, const minikv_f16 *q, const minikv_
     return launch_decode(*s, q, *c, sm_scale, out, workspace, g_variant.load(), (hipStream_t)stream);
 }
 
+size_t kv_select_workspace_bytes(int32_t units, int32_t rep, int64_t L)
+{
+    if (units <= 0 || rep <= 1 || L <= 0) return 0;
+    return (size_t)units * (size_t)L * sizeof(uint32_t);        // one summed-score key per (unit, token)
+}
+
+int kv_select_hh_rw(int32_t units, int32_t rep, int64_t L, const float *A_cumul, const int32_t *n_hh,
+                    const int32_t *n_rw, int32_t *idx, int64_t idx_stride, int32_t *n_tok, void *workspace,
+                    size_t workspace_bytes, void *stream)
+{
+    if (units < 0 || rep < 1 || L < 0 || L > ((int64_t)1 << 30) || idx_stride < 0) return MINIKV_EINVAL;
+    if (units == 0) return MINIKV_OK;
+    if (!n_hh || !n_rw || !idx || !n_tok || ((uintptr_t)idx & 3u) || ((uintptr_t)n_tok & 3u)) return MINIKV_EINVAL;
+    if (L > 0 && (!A_cumul || ((uintptr_t)A_cumul & 3u))) return MINIKV_EINVAL;
+    const size_t need = kv_select_workspace_bytes(units, rep, L);
+    if (need && (!workspace || ((uintptr_t)workspace & 3u))) return MINIKV_EINVAL;
+    if (workspace_bytes < need) return MINIKV_EWORKSPACE;
+    return launch_select(units, rep, L, A_cumul, n_hh, n_rw, idx, idx_stride, n_tok, workspace,
+                         (hipStream_t)stream);
+}
+
+int kv_pyramid_budget(int32_t n_layers, double x, int32_t d, int32_t bottom_heavy, double *budget)
+{
+    if (n_layers < 1 || d < 1 || !(x >= 0.0) || !budget) return MINIKV_EINVAL;
+    const double small_end = x / d, large_end = 2.0 * x - x / d;
+    const double first = bottom_heavy ? large_end : small_end, last = bottom_heavy ? small_end : large_end;
+    for (int32_t l = 0; l < n_layers; ++l)
+        budget[l] = n_layers == 1 ? x : first + (last - first) * l / (n_layers - 1);
+    return MINIKV_OK;
+}
+
 int minikv_set_variant(int variant)
 {
     if (variant < 0 || variant > 4 || variant == 2) return MINIKV_EINVAL;

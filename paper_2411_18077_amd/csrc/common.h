@@ -77,4 +77,8 @@ int launch_append(const minikv_shape &s, const minikv_f16 *k_new, const minikv_f
 int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
                   minikv_f16 *out, void *workspace, int variant, hipStream_t st);
 
+int launch_select(int32_t units, int32_t rep, int64_t L, const float *A, const int32_t *n_hh,
+                  const int32_t *n_rw, int32_t *idx, int64_t idx_stride, int32_t *n_tok, void *workspace,
+                  hipStream_t st);
+
 }  // namespace minikv

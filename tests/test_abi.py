@@ -24,7 +24,8 @@ def test_exports_every_declared_symbol(api):
     names = re.findall(r"\b(minikv_\w+|kv_\w+)\s*\(", text)
     names = sorted(set(names))
     assert {"kv_quantize_pack", "kv_append_residual", "kv_flush_residual", "minikv_decode_attn",
-            "minikv_workspace_bytes", "minikv_buffer_bytes", "minikv_abi_version"} <= set(names)
+            "minikv_workspace_bytes", "minikv_buffer_bytes", "minikv_abi_version", "kv_select_hh_rw",
+            "kv_select_workspace_bytes", "kv_pyramid_budget"} <= set(names)
     l = api.lib()
     for n in names:
         assert hasattr(l, n), n
@@ -76,3 +77,37 @@ def test_pointer_and_workspace_checks(api):
     assert l.kv_quantize_pack(C.byref(s), P(0x1000), P(0x1000), 64, None, 0, P(0x1000), 0, C.byref(good), None) == 0
     assert l.minikv_set_variant(99) == -1 and l.minikv_set_variant(2) == -1 and l.minikv_set_variant(0) == 0
     assert b"workspace" in l.minikv_strerror(-3)
+
+
+def test_selection_arguments_are_checked_on_the_host(api):
+    l, P = api.lib(), C.c_void_p
+    ok = [P(0x1000)] * 5                                     # A_cumul, n_hh, n_rw, idx (stride follows), n_tok
+    call = lambda units, rep, L, A, hh, rw, idx, stride, ntok, ws, wsb: l.kv_select_hh_rw(
+        units, rep, L, A, hh, rw, idx, stride, ntok, ws, wsb, None)
+    assert call(0, 1, 64, None, None, None, None, 64, None, None, 0) == 0            # no units: nothing to do
+    assert call(-1, 1, 64, *ok[:4], 64, ok[4], None, 0) == -1
+    assert call(4, 0, 64, *ok[:4], 64, ok[4], None, 0) == -1                         # rep < 1
+    assert call(4, 1, -1, *ok[:4], 64, ok[4], None, 0) == -1
+    assert call(4, 1, (1 << 30) + 1, *ok[:4], 64, ok[4], None, 0) == -1
+    assert call(4, 1, 64, None, *ok[1:4], 64, ok[4], None, 0) == -1                  # null scores
+    assert call(4, 1, 64, P(0x1002), *ok[1:4], 64, ok[4], None, 0) == -1             # misaligned scores
+    assert call(4, 1, 64, ok[0], None, *ok[2:4], 64, ok[4], None, 0) == -1
+    assert call(4, 1, 64, *ok[:4], -1, ok[4], None, 0) == -1
+    assert call(4, 4, 64, *ok[:4], 64, ok[4], None, 0) == -1                         # rep > 1 needs a workspace
+    assert call(4, 4, 64, *ok[:4], 64, ok[4], P(0x1000), 4 * 64 * 4 - 1) == -3
+    assert api.kv_select_workspace_bytes(4, 4, 64) == 4 * 64 * 4
+    assert api.kv_select_workspace_bytes(4, 1, 64) == 0 and api.kv_select_workspace_bytes(0, 4, 64) == 0
+
+
+def test_pyramid_budget_is_host_arithmetic_and_matches_the_oracle(api):
+    """The one entry point that runs entirely on the host: compared with the oracle here, without a GPU."""
+    from oracle import ref
+    for n_layers, x, d in [(32, 1024.0, 7), (32, 8192.0, 7), (2, 10.0, 7), (40, 333.0, 3), (1, 77.0, 7), (5, 0.0, 2)]:
+        for bottom_heavy in (1, 0):
+            got = api.kv_pyramid_budget(n_layers, x, d, bottom_heavy)
+            want = ref.pyramid_budget(n_layers, x, d, bool(bottom_heavy))
+            assert len(got) == n_layers
+            assert max(abs(a - b) for a, b in zip(got, want)) <= 1e-12 * max(x, 1.0)
+    for bad in [(0, 1.0, 7, 1), (4, -1.0, 7, 1), (4, float("nan"), 7, 1), (4, 1.0, 0, 1)]:
+        with pytest.raises(api.MinikvError):
+            api.kv_pyramid_budget(*bad)
