@@ -266,6 +266,31 @@ def main():
         torch.cuda.synchronize()
         result["flush_residual"] = {"ms": round(a.elapsed_time(b), 4), "tokens_per_unit": w.Rcap,
                                     "amortised_us_per_step": round(a.elapsed_time(b) * 1e3 / w.Rcap, 3)}
+        # prefill-side token selection on this workload's shape: each unit keeps as many tokens as its cache
+        # holds, half of them heavy hitters and half recent window, from synthetic cumulative attention scores
+        rep = w.Hq // w.Hkv
+        A = W.make_scores(w.units * rep, w.L, seed=w.seed + 5, device="cuda", kind="attention")
+        n_hh = (inp.n_tok // 2 // w.G * w.G).to(torch.int32)
+        n_rw = (inp.n_tok - n_hh).to(torch.int32)
+        stride = int(inp.n_tok.max())
+        sel_idx = torch.empty(w.units, stride, dtype=torch.int32, device="cuda")
+        sel_n = torch.empty(w.units, dtype=torch.int32, device="cuda")
+        nws = api.kv_select_workspace_bytes(w.units, rep, w.L)
+        sel_ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")
+        reps = 10
+        for i in range(2 + reps):
+            if i == 2:
+                a.record()
+            api.kv_select_hh_rw(w.units, rep, w.L, A, n_hh, n_rw, sel_idx, stride, sel_n, sel_ws)
+        b.record()
+        torch.cuda.synchronize()
+        sel_us = a.elapsed_time(b) * 1e3 / reps
+        sel_bytes = W.selection_bytes(w.units, rep, w.L, sel_n.cpu().tolist())
+        result["select_hh_rw"] = {
+            "what": "kv_select_hh_rw on this shape (sum of the group's query heads, top n_hh by score + recent "
+                    "window, ascending positions), mean of %d back-to-back calls" % reps,
+            "us": round(sel_us, 2), "bytes": sel_bytes, "GB/s": round(sel_bytes / sel_us / 1e3, 1),
+        }
         result["build_s"] = round(t_build, 1)
 
     print(json.dumps(result))
