@@ -481,3 +481,62 @@ int kv_pyramid_budget_ref(int32_t n_layers, double x, int32_t d, int32_t bottom_
         budget[l] = first + (last - first) * (double)l / (double)(n_layers - 1);
     return 0;
 }
+
+/* ---------------------------------------------------------------------------------------------------
+ * Prefill attention with cumulative attention scores: Section 3.2, Algorithm 1 line 2, eq. (1) (causal).
+ * ------------------------------------------------------------------------------------------------- */
+int selective_flash_attn_ref(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, int32_t D, const uint16_t *Q,
+                             const uint16_t *K, const uint16_t *V, float sm_scale, uint16_t *XO_f16,
+                             double *XO_f64, double *lse, double *A_cumul)
+{
+    if (B < 0 || Hq < 1 || Hkv < 1 || Hq % Hkv || L < 0 || D < 1 || !Q || !K || !V) return -1;
+    const int rep = Hq / Hkv;
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bh = 0; bh < (long)B * Hq; ++bh) {
+        const long b = bh / Hq, hq = bh % Hq, hk = hq / rep;
+        const uint16_t *q = Q + (size_t)bh * (size_t)L * (size_t)D;
+        const uint16_t *k = K + ((size_t)b * Hkv + (size_t)hk) * (size_t)L * (size_t)D;
+        const uint16_t *v = V + ((size_t)b * Hkv + (size_t)hk) * (size_t)L * (size_t)D;
+        double *p = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
+        double *o = (double *)malloc(sizeof(double) * (size_t)D);
+        if (!p || !o) {
+            failed = 1;
+            free(p);
+            free(o);
+            continue;
+        }
+        if (A_cumul)
+            for (int64_t j = 0; j < L; ++j) A_cumul[(size_t)bh * (size_t)L + (size_t)j] = 0.0;
+        for (int64_t i = 0; i < L; ++i) {
+            double m = -INFINITY;
+            for (int64_t j = 0; j <= i; ++j) {                 /* causal: keys up to the query's own position */
+                double s = 0.0;
+                for (int c = 0; c < D; ++c)
+                    s += (double)ref_f16_to_f32(q[i * D + c]) * (double)ref_f16_to_f32(k[j * D + c]);
+                p[j] = s * (double)sm_scale;
+                if (p[j] > m) m = p[j];
+            }
+            double sum = 0.0;
+            for (int64_t j = 0; j <= i; ++j) {
+                p[j] = exp(p[j] - m);
+                sum += p[j];
+            }
+            for (int c = 0; c < D; ++c) o[c] = 0.0;
+            for (int64_t j = 0; j <= i; ++j) {
+                p[j] /= sum;
+                for (int c = 0; c < D; ++c) o[c] += p[j] * (double)ref_f16_to_f32(v[j * D + c]);
+                if (A_cumul) A_cumul[(size_t)bh * (size_t)L + (size_t)j] += p[j];
+            }
+            const size_t row = ((size_t)bh * (size_t)L + (size_t)i);
+            if (lse) lse[row] = m + log(sum);
+            for (int c = 0; c < D; ++c) {
+                if (XO_f64) XO_f64[row * (size_t)D + (size_t)c] = o[c];
+                if (XO_f16) XO_f16[row * (size_t)D + (size_t)c] = ref_f64_to_f16(o[c]);
+            }
+        }
+        free(p);
+        free(o);
+    }
+    return failed ? -1 : 0;
+}

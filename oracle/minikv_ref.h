@@ -27,8 +27,9 @@
  * fp64 exact attention on a separately dequantized cache, softmax rows summing to 1, T=0 and r=0
  * special cases, uniform-weight case, GQA == replicated MHA, unit permutation; for the token selection:
  * a library sort with explicit tie keys, monotone / constant score closed forms, exhaustive tiny cases,
- * boundary budgets, pre-summed heads; for the pyramid budget: mean, end points, linearity.  No function
- * here is "parity unpinned".
+ * boundary budgets, pre-summed heads; for the pyramid budget: mean, end points, linearity; for the prefill
+ * attention: a numpy matmul + softmax, equal keys (harmonic-number column sums), rows summing to one,
+ * first and last token, GQA == replicated MHA.  No function here is "parity unpinned".
  */
 #ifndef MINIKV_REF_H
 #define MINIKV_REF_H
@@ -84,6 +85,20 @@ int kv_flush_residual_ref(const ref_shape *s, ref_cache *c);
  * probs [B*Hq][Tcap+Rcap] softmax weights, quantized tokens first then residual (may be NULL). */
 int minikv_decode_attn_ref(const ref_shape *s, const uint16_t *q, const ref_cache *c, float sm_scale,
                            uint16_t *out_f16, double *out_f64, double *probs);
+
+/* Section 3.2 (the two outputs of the selective attention kernel) + Algorithm 1 line 2, with the attention
+ * of Appendix A eq. (1) restricted to the causal part (query i sees keys 0..i): for every batch b and query
+ * head hq (reading KV head hq / (Hq/Hkv)), in fp64 from the fp16 inputs,
+ *   P[i][j]    = softmax_j(sm_scale * Q[i].K[j]),  j <= i
+ *   X_O[i]     = sum_j P[i][j] V[j]                         (XO_f16: rounded once to fp16; XO_f64: not rounded)
+ *   lse[i]     = log sum_j exp(sm_scale * Q[i].K[j])        (natural logarithm)
+ *   A_cumul[j] = sum_{i >= j} P[i][j]                       (column sums of the attention matrix)
+ * Q [B][Hq][L][D], K, V [B][Hkv][L][D] fp16; outputs [B][Hq][L][D] and [B][Hq][L]; any output may be NULL.
+ * The full matrix is never stored (one row at a time), but nothing is tiled or reordered.
+ * Returns 0, or -1 on bad arguments. */
+int selective_flash_attn_ref(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, int32_t D, const uint16_t *Q,
+                             const uint16_t *K, const uint16_t *V, float sm_scale, uint16_t *XO_f16,
+                             double *XO_f64, double *lse, double *A_cumul);
 
 /* Section 3.1.2 (heavy hitters and recent window) + Algorithm 1 line 3.  For every unit u the score of
  * prompt token i is the binary32 sum, query heads in ascending order, of the rep rows

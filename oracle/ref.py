@@ -37,7 +37,8 @@ def lib():
         _lib.ref_group_bytes.argtypes = [C.c_int]
         for name in ("ref_check_shape", "kv_quantize_pack_ref", "kv_append_residual_ref",
                      "kv_flush_residual_ref", "minikv_decode_attn_ref", "ref_unpack_codes", "ref_dequant",
-                     "ref_k_meta_pos", "kv_select_hh_rw_ref", "kv_pyramid_budget_ref"):
+                     "ref_k_meta_pos", "kv_select_hh_rw_ref", "kv_pyramid_budget_ref",
+                     "selective_flash_attn_ref"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -127,6 +128,25 @@ def decode_attn(cache: RefCache, q, sm_scale, want_f64=False, want_probs=False):
     if rc:
         raise RuntimeError("minikv_decode_attn_ref failed: %d" % rc)
     return out16, out64, probs
+
+
+def selective_flash_attn(Q, K, V, sm_scale):
+    """Q float16 [B, Hq, L, D]; K, V float16 [B, Hkv, L, D] -> (X_O float16, X_O float64, lse float64 [B, Hq, L],
+    A_cumul float64 [B, Hq, L])."""
+    Q, K, V = _f16(Q), _f16(K), _f16(V)
+    B, Hq, L, D = Q.shape
+    Hkv = K.shape[1]
+    assert K.shape == (B, Hkv, L, D) and V.shape == K.shape
+    xo16 = np.zeros((B, Hq, L, D), np.float16)
+    xo64 = np.zeros((B, Hq, L, D), np.float64)
+    lse = np.zeros((B, Hq, L), np.float64)
+    acc = np.zeros((B, Hq, L), np.float64)
+    rc = lib().selective_flash_attn_ref(C.c_int32(B), C.c_int32(Hq), C.c_int32(Hkv), C.c_int64(L), C.c_int32(D),
+                                        _p(Q), _p(K), _p(V), C.c_float(sm_scale), _p(xo16), _p(xo64), _p(lse),
+                                        _p(acc))
+    if rc:
+        raise RuntimeError("selective_flash_attn_ref failed: %d" % rc)
+    return xo16, xo64, lse, acc
 
 
 def select_hh_rw(A_cumul, n_hh, n_rw, rep=1, idx_stride=None):
