@@ -132,6 +132,23 @@ int minikv_decode_attn(const minikv_shape *shape, const minikv_f16 *q, const min
                        float sm_scale, minikv_f16 *out, void *workspace, size_t workspace_bytes,
                        void *stream);
 
+/* Section 3.2 (selective flash attention) / Algorithm 1 line 2: causal attention of the prompt with itself that
+ * also returns the cumulative attention score of every prompt token, in memory linear in L.  For batch b and
+ * query head hq (reading KV head hq / (Hq/Hkv)), with P[i][j] = softmax_j(sm_scale * Q[i].K[j]) over j <= i:
+ *   X_O[i]     = sum_j P[i][j] V[j]                      (fp16)
+ *   lse[i]     = log sum_{j<=i} exp(sm_scale * Q[i].K[j])  (fp32, natural logarithm)
+ *   A_cumul[j] = sum_{i>=j} P[i][j]                      (fp32; the rows kv_select_hh_rw takes)
+ * Two passes as in Section 3.2: row blocks in parallel for X_O and lse, then column blocks in parallel that
+ * recompute the scores and normalise them with lse.  fp16 operands, fp32 accumulation.
+ *   Q          fp16 [B][Hq][L][128]                       (device, read)
+ *   K, V       fp16 [B][Hkv][L][128]                      (device, read)
+ *   X_O        fp16 [B][Hq][L][128]; lse fp32 [B][Hq][L]  (device, written)
+ *   A_cumul    fp32 [B][Hq][L] or NULL (then only the first pass runs)   (device, written)
+ * No workspace.  L >= 1, Hq % Hkv == 0, pointers 16-byte aligned, sm_scale finite. */
+int selective_flash_attn(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, const minikv_f16 *Q, const minikv_f16 *K,
+                         const minikv_f16 *V, float sm_scale, minikv_f16 *X_O, float *lse, float *A_cumul,
+                         void *stream);
+
 /* Section 3.1.2 (heavy hitters vs. recent window) / Algorithm 1 line 3: which prompt tokens a unit keeps.
  * The score of prompt token i of unit u is the binary32 sum, query heads in ascending order, of the rep
  * rows A_cumul[(u*rep + h)*L + i] (the cumulative attention score of Algorithm 1 line 2; under grouped-query

@@ -1,0 +1,291 @@
+// Prefill attention that also returns the cumulative attention score of every prompt token, in memory linear
+// in the prompt length (Section 3.2; Algorithm 1 line 2): X_O = softmax(sm_scale Q K^T) V on the causal part,
+// LSE per query row, A_cumul = column sums of the softmax matrix.
+//
+// Two kernels, as in Section 3.2, re-tiled for 64-lane waves and the 32x32x16 fp16 matrix instruction:
+//   prefill_fwd_kernel     row blocks in parallel.  A workgroup of 4 waves owns 128 queries (32 per wave) and
+//                          walks the keys in tiles of 64 through LDS.  Scores are computed TRANSPOSED,
+//                          S^T = K Q^T, so that a lane holds one query column: the running max / sum of the
+//                          online softmax are per-lane scalars (one exchange between the two half-waves per
+//                          tile), the rescale of the output is a per-lane multiply, and the fp32 scores, once
+//                          turned into fp16 weights, ARE the B operand of O^T = V^T P^T without any shuffle
+//                          (the key order inside a 16-key step is whatever the accumulator layout gives; the
+//                          V^T operand is read in the same order).  V is transposed on its way into LDS.
+//   prefill_colsum_kernel  column blocks in parallel.  A workgroup owns 128 keys (32 per wave, their K rows
+//                          held in registers as the B operand), walks the queries from the diagonal down in
+//                          tiles of 64 through LDS, recomputes S = Q K^T, normalises with the saved LSE and
+//                          adds the weights of its key column in the lane: no atomics, one exchange at the end.
+#include "common.h"
+
+namespace minikv {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+constexpr int kPfD = 128;            // head dimension
+constexpr int kPfM = 128;            // queries per workgroup (forward) / keys per workgroup (column sums)
+constexpr int kPfN = 64;             // keys (forward) / queries (column sums) per LDS tile
+constexpr int kPfKRow = kPfD + 8;    // halves per row of a row-major tile in LDS (16-byte pad)
+constexpr int kPfVRow = kPfN + 8;    // halves per row of the transposed V tile in LDS
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct PrefillArgs {
+    const _Float16 *Q, *K, *V;
+    _Float16 *XO;
+    float *lse, *A_cumul;
+    int Hq, rep, nblk;
+    long L;
+    float scale_log2;                // sm_scale * log2(e): the softmax runs on powers of two
+};
+
+__device__ __forceinline__ float16v mfma32(half8 a, half8 b, float16v c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
+// Row of accumulator element i (0..15) inside a 32x32 result tile, for a lane of half-wave g.
+__device__ __forceinline__ int acc_row(int i, int g) { return (i >> 2) * 8 + g * 4 + (i & 3); }
+
+// One tile of 64 rows x 128 halves from global memory: 4 chunks of 16 bytes per thread, coalesced.  Rows at or
+// beyond `rows_valid` are read from the last valid row (their products are masked or discarded later).
+struct TileRegs {
+    uint4 c[4];
+};
+__device__ __forceinline__ TileRegs load_tile(const _Float16 *base, long row0, long rows_valid, int tid)
+{
+    TileRegs t;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int chunk = tid + 256 * i;                 // row = chunk / 16, 8 halves at (chunk % 16) * 8
+        long row = row0 + (chunk >> 4);
+        row = row < rows_valid ? row : rows_valid - 1;
+        t.c[i] = *(const uint4 *)(base + row * kPfD + (chunk & 15) * 8);
+    }
+    return t;
+}
+__device__ __forceinline__ void store_tile_rowmajor(_Float16 *lds, const TileRegs &t, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int chunk = tid + 256 * i;
+        *(uint4 *)(lds + (chunk >> 4) * kPfKRow + (chunk & 15) * 8) = t.c[i];
+    }
+}
+// The same chunks written transposed: lds[d][key].
+__device__ __forceinline__ void store_tile_transposed(_Float16 *lds, const TileRegs &t, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int chunk = tid + 256 * i;
+        const int key = chunk >> 4, d0 = (chunk & 15) * 8;
+        const half8 v = *(const half8 *)&t.c[i];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) lds[(d0 + j) * kPfVRow + key] = v[j];
+    }
+}
+
+__global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
+{
+    __shared__ __align__(16) _Float16 Ks[kPfN * kPfKRow];
+    __shared__ __align__(16) _Float16 Vt[kPfD * kPfVRow];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, g = lane >> 5;
+    // heaviest row blocks (the last ones: they see the most keys) first
+    const int nbh = gridDim.x / a.nblk;
+    const int qb = a.nblk - 1 - (int)(blockIdx.x / nbh);
+    const long bh = blockIdx.x % nbh;
+    const long kvh = (bh / a.Hq) * (a.Hq / a.rep) + (bh % a.Hq) / a.rep;
+    const long L = a.L;
+    const _Float16 *Qh = a.Q + bh * L * kPfD, *Kh = a.K + kvh * L * kPfD, *Vh = a.V + kvh * L * kPfD;
+
+    const long q0 = (long)qb * kPfM + wave * 32;       // first query of this wave
+    const long query = q0 + r;                         // this lane's query column
+    const long qrow = query < L ? query : L - 1;
+    half8 qf[8];                                       // B operand of S^T = K Q^T: Q[query][16 ks + 8 g ..]
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const half8 *)(Qh + qrow * kPfD + ks * 16 + g * 8);
+
+    float16v o[4];                                     // O^T: o[db][i] = out[query][32 db + acc_row(i, g)]
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] = 0.0f;
+    float m = -INFINITY, l = 0.0f;                     // running max (shared by both half-waves), this lane's part of the sum
+
+    const long kend = min((long)(qb + 1) * kPfM, L);   // keys 0 .. kend-1 are visible to some query of the block
+    const int ntiles = (int)((kend + kPfN - 1) / kPfN);
+    TileRegs kr = load_tile(Kh, 0, L, tid), vr = load_tile(Vh, 0, L, tid);
+    for (int n = 0; n < ntiles; ++n) {
+        __syncthreads();                               // every wave is done with the previous tile
+        store_tile_rowmajor(Ks, kr, tid);
+        store_tile_transposed(Vt, vr, tid);
+        __syncthreads();
+        if (n + 1 < ntiles) {
+            kr = load_tile(Kh, (long)(n + 1) * kPfN, L, tid);
+            vr = load_tile(Vh, (long)(n + 1) * kPfN, L, tid);
+        }
+        const long key0 = (long)n * kPfN;
+        if (key0 > q0 + 31) continue;                  // no query of this wave sees the tile (uniform in the wave)
+
+        float16v s[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[t][i] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const half8 kf = *(const half8 *)(Ks + (t * 32 + r) * kPfKRow + ks * 16 + g * 8);
+                s[t] = mfma32(kf, qf[ks], s[t]);
+            }
+        }
+        const bool diag = key0 + kPfN - 1 > q0;        // some (key, query) pair of the tile is above the diagonal
+        float mx = m;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float v = s[t][i] * a.scale_log2;
+                if (diag && key0 + t * 32 + acc_row(i, g) > query) v = -INFINITY;
+                s[t][i] = v;
+                mx = fmaxf(mx, v);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));        // the other half-wave holds the other 32 keys of the column
+        const float alpha = __builtin_amdgcn_exp2f(m - mx);             // m = -inf at the first tile: alpha = 0, nothing to rescale
+        m = mx;
+        float psum = 0.0f;
+        half8 pb[2][2];                                // B operands of O^T += V^T P^T, 16 keys each
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float p = __builtin_amdgcn_exp2f(s[t][i] - mx);
+                psum += p;
+                pb[t][i >> 3][i & 7] = (_Float16)p;
+            }
+        l = l * alpha + psum;
+        if (__any(alpha != 1.0f)) {
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int sx = 0; sx < 2; ++sx)
+#pragma unroll
+                for (int db = 0; db < 4; ++db) {
+                    // keys of this step in accumulator order: 32 t + 16 sx + 4 g + {0..3} and the same + 8
+                    const _Float16 *vp = Vt + (db * 32 + r) * kPfVRow + t * 32 + sx * 16 + g * 4;
+                    const half4 lo = *(const half4 *)vp, hi = *(const half4 *)(vp + 8);
+                    const half8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    o[db] = mfma32(vf, pb[t][sx], o[db]);
+                }
+    }
+
+    l += __shfl_xor(l, 32, 64);
+    const float inv = 1.0f / l;
+    if (query < L) {
+        if (g == 0) a.lse[bh * L + query] = (m + log2f(l)) * kLn2;
+        _Float16 *orow = a.XO + (bh * L + query) * kPfD;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int iq = 0; iq < 4; ++iq) {
+                half4 h;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) h[j] = (_Float16)(o[db][iq * 4 + j] * inv);
+                *(half4 *)(orow + db * 32 + iq * 8 + g * 4) = h;
+            }
+    }
+}
+
+__global__ __launch_bounds__(256, 2) void prefill_colsum_kernel(PrefillArgs a)
+{
+    __shared__ __align__(16) _Float16 Qs[kPfN * kPfKRow];
+    __shared__ __align__(16) float lse2[kPfN];         // LSE of the tile's queries, in powers of two
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, g = lane >> 5;
+    // column blocks in natural order: block 0 is seen by every query and is the heaviest
+    const int nbh = gridDim.x / a.nblk;
+    const int kb = (int)(blockIdx.x / nbh);
+    const long bh = blockIdx.x % nbh;
+    const long kvh = (bh / a.Hq) * (a.Hq / a.rep) + (bh % a.Hq) / a.rep;
+    const long L = a.L;
+    const _Float16 *Qh = a.Q + bh * L * kPfD, *Kh = a.K + kvh * L * kPfD;
+    const float *lseh = a.lse + bh * L;
+
+    const long k0 = (long)kb * kPfM + wave * 32;       // first key of this wave
+    const long key = k0 + r;                           // this lane's key column
+    const long krow = key < L ? key : L - 1;
+    half8 kf[8];                                       // B operand of S = Q K^T: K[key][16 ks + 8 g ..]
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) kf[ks] = *(const half8 *)(Kh + krow * kPfD + ks * 16 + g * 8);
+
+    float colsum = 0.0f;
+    const int tile0 = (int)(((long)kb * kPfM) / kPfN), ntiles = (int)((L + kPfN - 1) / kPfN);
+    TileRegs qr = load_tile(Qh, (long)tile0 * kPfN, L, tid);
+    float lr = 0.0f;
+    if (tid < kPfN) lr = lseh[min((long)tile0 * kPfN + tid, L - 1)];
+    for (int n = tile0; n < ntiles; ++n) {
+        __syncthreads();
+        store_tile_rowmajor(Qs, qr, tid);
+        if (tid < kPfN) lse2[tid] = lr * kLog2e;
+        __syncthreads();
+        if (n + 1 < ntiles) {
+            qr = load_tile(Qh, (long)(n + 1) * kPfN, L, tid);
+            if (tid < kPfN) lr = lseh[min((long)(n + 1) * kPfN + tid, L - 1)];
+        }
+        const long qt0 = (long)n * kPfN;
+        if (qt0 + kPfN - 1 < k0) continue;             // every query of the tile precedes every key of this wave
+        const bool edge = qt0 < k0 + 31 || qt0 + kPfN > L;   // the diagonal or the end of the prompt crosses the tile
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            float16v s;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[i] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const half8 qf = *(const half8 *)(Qs + (t * 32 + r) * kPfKRow + ks * 16 + g * 8);
+                s = mfma32(qf, kf[ks], s);
+            }
+#pragma unroll
+            for (int iq = 0; iq < 4; ++iq) {
+                const float4 ls = *(const float4 *)&lse2[t * 32 + iq * 8 + g * 4];
+                const float lsv[4] = {ls.x, ls.y, ls.z, ls.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const long q = qt0 + t * 32 + iq * 8 + g * 4 + j;
+                    float p = __builtin_amdgcn_exp2f(s[iq * 4 + j] * a.scale_log2 - lsv[j]);
+                    if (edge && (q < key || q >= L)) p = 0.0f;
+                    colsum += p;
+                }
+            }
+        }
+    }
+    colsum += __shfl_xor(colsum, 32, 64);
+    if (g == 0 && key < L) a.A_cumul[bh * L + key] = colsum;
+}
+
+int launch_prefill(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, const minikv_f16 *Q, const minikv_f16 *K,
+                   const minikv_f16 *V, float sm_scale, minikv_f16 *XO, float *lse, float *A_cumul,
+                   hipStream_t st)
+{
+    PrefillArgs a;
+    a.Q = (const _Float16 *)Q, a.K = (const _Float16 *)K, a.V = (const _Float16 *)V;
+    a.XO = (_Float16 *)XO, a.lse = lse, a.A_cumul = A_cumul;
+    a.Hq = Hq, a.rep = Hq / Hkv, a.L = L, a.scale_log2 = sm_scale * kLog2e;
+    a.nblk = (int)((L + kPfM - 1) / kPfM);
+    const long blocks = (long)B * Hq * a.nblk;
+    hipLaunchKernelGGL(prefill_fwd_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
+    if (hipGetLastError() != hipSuccess) return MINIKV_ELAUNCH;
+    if (A_cumul) {
+        hipLaunchKernelGGL(prefill_colsum_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
+        if (hipGetLastError() != hipSuccess) return MINIKV_ELAUNCH;
+    }
+    return MINIKV_OK;
+}
+
+}  // namespace minikv

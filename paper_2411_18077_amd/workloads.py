@@ -151,6 +151,25 @@ def make_inputs(w: Workload, device="cpu", seed_offset=0, unit_chunk=None):
     return Inputs(w, K, V, idx, n_tok.to(dev), q, Rk, Rv, Tcap, out_ch)
 
 
+def make_prefill_inputs(B, Hq, Hkv, L, seed, device="cpu", D=128, gain=1.0):
+    """fp16 Q [B, Hq, L, D], K and V [B, Hkv, L, D] of a prompt: N(0,1) draws (Q and K times `gain`, which makes
+    the softmax rows more peaked), as the projections of a real prompt are not available."""
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    Q = (torch.randn(B, Hq, L, D, generator=gen, device=dev) * gain).to(torch.float16)
+    K = (torch.randn(B, Hkv, L, D, generator=gen, device=dev) * gain).to(torch.float16)
+    V = torch.randn(B, Hkv, L, D, generator=gen, device=dev).to(torch.float16)
+    return Q, K, V
+
+
+def prefill_flops(B, Hq, L, D=128):
+    """Floating-point operations of the two passes on the causal part: L(L+1)/2 (query, key) pairs per head,
+    2D for a score and 2D for its share of the output in the first pass, 2D for the score again in the second."""
+    pairs = L * (L + 1) // 2
+    return B * Hq * pairs * (2 * D + 2 * D + 2 * D)
+
+
 def make_scores(rows, L, seed, device="cpu", kind="attention"):
     """fp32 [rows, L] stand-ins for the cumulative attention score of each prompt token (the column sums
     of a causal attention map, one row per query head).  Real maps need a model; these have their shape:

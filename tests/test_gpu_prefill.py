@@ -1,0 +1,146 @@
+"""GPU parity of the prefill attention with cumulative attention scores (Section 3.2, Algorithm 1 line 2)
+against the fp64 oracle: X_O to 2e-3, LSE to 1e-3, A_cumul to 1e-3 relative (+1e-4 absolute); then
+Algorithm 1 lines 2-5 and 17-19 chained on the GPU and checked stage by stage."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2411_18077_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+TOL_O, TOL_LSE, RTOL_A, ATOL_A = 2e-3, 1e-3, 1e-3, 1e-4
+
+
+@pytest.fixture(scope="module")
+def g():
+    import gpu_common
+    assert torch.cuda.is_available()
+    return gpu_common
+
+
+def run_gpu(Q, K, V, sm, want_cumul=True):
+    from paper_2411_18077_amd import api
+    B, Hq, L, D = Q.shape
+    xo = torch.full((B, Hq, L, D), float("nan"), dtype=torch.float16, device="cuda")
+    lse = torch.full((B, Hq, L), float("nan"), dtype=torch.float32, device="cuda")
+    acc = torch.full((B, Hq, L), float("nan"), dtype=torch.float32, device="cuda") if want_cumul else None
+    api.selective_flash_attn(B, Hq, K.shape[1], L, Q, K, V, sm, xo, lse, acc)
+    torch.cuda.synchronize()
+    return xo, lse, acc
+
+
+def check(g, B, Hq, Hkv, L, seed, gain=1.0, sm=None):
+    from oracle import ref
+    sm = 1.0 / math.sqrt(128) if sm is None else sm
+    Q, K, V = W.make_prefill_inputs(B, Hq, Hkv, L, seed, device="cuda", gain=gain)
+    xo, lse, acc = run_gpu(Q, K, V, sm)
+    _, xo64, lse64, acc64 = ref.selective_flash_attn(g.to_np(Q), g.to_np(K), g.to_np(V), sm)
+    got_o, got_l, got_a = (g.to_np(t).astype(np.float64) for t in (xo, lse, acc))
+    assert np.isfinite(got_o).all() and np.isfinite(got_l).all() and np.isfinite(got_a).all()
+    assert np.max(np.abs(got_o - xo64)) <= TOL_O
+    assert np.max(np.abs(got_l - lse64)) <= TOL_LSE
+    assert np.all(np.abs(got_a - acc64) <= RTOL_A * np.abs(acc64) + ATOL_A)
+    assert np.allclose(got_a.sum(-1), L, rtol=1e-4)          # the rows of the attention matrix sum to one
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,L", [(1, 1, 1, 1), (1, 2, 1, 31), (1, 1, 1, 64), (1, 2, 2, 65), (1, 1, 1, 128),
+                                         (2, 4, 2, 129), (1, 8, 2, 300), (1, 2, 1, 777), (1, 4, 4, 1024)])
+def test_prefill_matches_the_oracle(g, B, Hq, Hkv, L):
+    check(g, B, Hq, Hkv, L, seed=100 + L)
+
+
+@pytest.mark.parametrize("gain,sm", [(2.0, None), (1.0, 1.0), (0.0, None)])
+def test_peaked_and_flat_softmax_rows(g, gain, sm):
+    """gain 2: scores ~ N(0, 4^2/...) (peaked rows); sm_scale 1: very peaked; gain 0: all scores equal, so the
+    column sums are differences of harmonic numbers."""
+    check(g, 1, 4, 2, 500, seed=7, gain=gain, sm=sm)
+
+
+def test_first_pass_alone(g):
+    from oracle import ref
+    Q, K, V = W.make_prefill_inputs(1, 2, 1, 200, 5, device="cuda")
+    xo, lse, acc = run_gpu(Q, K, V, 0.09, want_cumul=False)
+    _, xo64, lse64, _ = ref.selective_flash_attn(g.to_np(Q), g.to_np(K), g.to_np(V), 0.09)
+    assert np.max(np.abs(g.to_np(xo).astype(np.float64) - xo64)) <= TOL_O
+    assert np.max(np.abs(g.to_np(lse).astype(np.float64) - lse64)) <= TOL_LSE
+
+
+def test_long_prompt_on_sampled_rows_and_columns(g):
+    """L = 8192 (the longest length of the paper's kernel tables), 32 query / 8 KV heads: the oracle would
+    need minutes for all of it, so a few heads are recomputed by it on a strided subset of the prompt:
+    every 37th query row (its X_O and LSE need only that row's scores), and the exact property sum_j
+    A_cumul[j] = L on all heads; A_cumul itself is compared on one head with numpy in float64."""
+    B, Hq, Hkv, L = 1, 32, 8, 8192
+    sm = 1.0 / math.sqrt(128)
+    Q, K, V = W.make_prefill_inputs(B, Hq, Hkv, L, 11, device="cuda")
+    xo, lse, acc = run_gpu(Q, K, V, sm)
+    assert np.allclose(g.to_np(acc).astype(np.float64).sum(-1), L, rtol=1e-4)
+    for hq in (0, 13, 31):
+        q = g.to_np(Q[0, hq]).astype(np.float64)
+        k = g.to_np(K[0, hq // 4]).astype(np.float64)
+        v = g.to_np(V[0, hq // 4]).astype(np.float64)
+        rows = np.arange(5, L, 37)
+        S = (q[rows] @ k.T) * np.float64(np.float32(sm))
+        S[np.arange(L)[None, :] > rows[:, None]] = -np.inf
+        m = S.max(-1, keepdims=True)
+        E = np.exp(S - m)
+        P = E / E.sum(-1, keepdims=True)
+        assert np.max(np.abs(g.to_np(xo[0, hq])[rows].astype(np.float64) - P @ v)) <= TOL_O
+        assert np.max(np.abs(g.to_np(lse[0, hq])[rows].astype(np.float64) - (m[:, 0] + np.log(E.sum(-1))))) <= TOL_LSE
+    # one head in full, in float64 with numpy, row block by row block (the matrix is 8192 x 8192)
+    hq = 7
+    q = g.to_np(Q[0, hq]).astype(np.float64); k = g.to_np(K[0, hq // 4]).astype(np.float64)
+    col = np.zeros(L)
+    for r0 in range(0, L, 1024):
+        rows = np.arange(r0, r0 + 1024)
+        S = (q[rows] @ k.T) * np.float64(np.float32(sm))
+        S[np.arange(L)[None, :] > rows[:, None]] = -np.inf
+        E = np.exp(S - S.max(-1, keepdims=True))
+        col += (E / E.sum(-1, keepdims=True)).sum(0)
+    got = g.to_np(acc[0, hq]).astype(np.float64)
+    assert np.all(np.abs(got - col) <= RTOL_A * np.abs(col) + ATOL_A)
+
+
+def test_prefill_select_quantize_decode_chain(g):
+    """Algorithm 1 lines 2-5, then a decode step (lines 9, 17-19), all on the GPU; each stage is checked
+    against the oracle fed with the GPU's input to that stage (the selection decides on the GPU's fp32
+    A_cumul on both sides, so the kept positions are bit-exact)."""
+    from paper_2411_18077_amd import api
+    from oracle import ref
+    B, Hq, Hkv, L, G = 2, 8, 2, 1024, 32
+    sm = 1.0 / math.sqrt(128)
+    Q, K, V = W.make_prefill_inputs(B, Hq, Hkv, L, 21, device="cuda")
+    xo, lse, acc = run_gpu(Q, K, V, sm)
+    _, xo64, _, acc64 = ref.selective_flash_attn(g.to_np(Q), g.to_np(K), g.to_np(V), sm)
+    assert np.max(np.abs(g.to_np(xo).astype(np.float64) - xo64)) <= TOL_O
+    assert np.all(np.abs(g.to_np(acc) - acc64) <= RTOL_A * np.abs(acc64) + ATOL_A)
+    U, rep = B * Hkv, Hq // Hkv
+    n_hh = torch.full((U,), 256, dtype=torch.int32, device="cuda")
+    n_rw = torch.full((U,), 256, dtype=torch.int32, device="cuda")
+    idx = torch.zeros(U, 512, dtype=torch.int32, device="cuda"); n_tok = torch.zeros(U, dtype=torch.int32, device="cuda")
+    ws = torch.empty(api.kv_select_workspace_bytes(U, rep, L), dtype=torch.uint8, device="cuda")
+    A2 = acc.view(U * rep, L)
+    api.kv_select_hh_rw(U, rep, L, A2, n_hh, n_rw, idx, 512, n_tok, ws)
+    ridx, rn = ref.select_hh_rw(g.to_np(A2), g.to_np(n_hh), g.to_np(n_rw), rep=rep, idx_stride=512)
+    assert np.array_equal(g.to_np(idx), ridx) and np.array_equal(g.to_np(n_tok), rn)
+    s = api.make_shape(B, Hq, Hkv, 128, G, 640, 32)
+    rs = ref.RefShape(B, Hq, Hkv, 128, G, 640, 32)
+    gc = api.Cache(s)
+    Ku, Vu = K.view(U, L, 128), V.view(U, L, 128)
+    api.kv_quantize_pack(s, Ku, Vu, L, idx, 512, n_tok, 512, gc)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(3)
+    kn = torch.randn(U, 128, generator=gen, device="cuda").to(torch.float16)
+    vn = torch.randn(U, 128, generator=gen, device="cuda").to(torch.float16)
+    qn = torch.randn(B, Hq, 128, generator=gen, device="cuda").to(torch.float16)
+    api.kv_append_residual(s, kn, vn, gc)
+    out = torch.empty(B, Hq, 128, dtype=torch.float16, device="cuda")
+    api.minikv_decode_attn(s, qn, gc, sm, out)
+    torch.cuda.synchronize()
+    rc = ref.RefCache(rs)
+    assert ref.quantize_pack(rc, g.to_np(Ku), g.to_np(Vu), rn, ridx) == 0
+    assert ref.append_residual(rc, g.to_np(kn), g.to_np(vn)) == 0
+    g.assert_cache_bit_exact(gc, rc, what=("Kc", "Ks", "Kz", "Vc", "Vs", "Vz", "q_len", "r_len"))
+    want, _, _ = ref.decode_attn(rc, g.to_np(qn), sm)
+    assert np.max(np.abs(g.to_np(out).astype(np.float64) - want)) <= 2e-3
