@@ -66,7 +66,10 @@ def lib():
         l.minikv_decode_attn.argtypes = [C.POINTER(MinikvShape), P, C.POINTER(MinikvCache), C.c_float, P, P,
                                          C.c_size_t, P]
         l.selective_flash_attn.restype = C.c_int
-        l.selective_flash_attn.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64, P, P, P, C.c_float, P, P, P, P]
+        l.selective_flash_attn.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64, P, P, P, C.c_float, P, P, P, P,
+                                           C.c_size_t, P]
+        l.selective_flash_attn_workspace_bytes.restype = C.c_size_t
+        l.selective_flash_attn_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int64]
         l.kv_select_workspace_bytes.restype = C.c_size_t
         l.kv_select_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int64]
         l.kv_select_hh_rw.restype = C.c_int
@@ -154,9 +157,15 @@ def minikv_decode_attn(shape, q, cache, sm_scale, out, workspace=None, stream=No
                                     ws.numel() * ws.element_size(), _stream(stream)), "minikv_decode_attn")
 
 
-def selective_flash_attn(B, Hq, Hkv, L, Q, K, V, sm_scale, X_O, lse, A_cumul, stream=None):
+def selective_flash_attn_workspace_bytes(B, Hkv, L):
+    return int(lib().selective_flash_attn_workspace_bytes(int(B), int(Hkv), int(L)))
+
+
+def selective_flash_attn(B, Hq, Hkv, L, Q, K, V, sm_scale, X_O, lse, A_cumul, workspace, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().selective_flash_attn(int(B), int(Hq), int(Hkv), int(L), _ptr(Q), _ptr(K), _ptr(V), float(sm_scale),
-                                      _ptr(X_O), _ptr(lse), _ptr(A_cumul), _stream(stream)), "selective_flash_attn")
+                                      _ptr(X_O), _ptr(lse), _ptr(A_cumul), _ptr(workspace), nbytes, _stream(stream)),
+           "selective_flash_attn")
 
 
 def kv_select_workspace_bytes(units, rep, L):

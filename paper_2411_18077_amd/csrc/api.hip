@@ -145,16 +145,24 @@ int minikv_decode_attn(const minikv_shape *s, const minikv_f16 *q, const minikv_
     return launch_decode(*s, q, *c, sm_scale, out, workspace, g_variant.load(), (hipStream_t)stream);
 }
 
+size_t selective_flash_attn_workspace_bytes(int32_t B, int32_t Hkv, int64_t L)
+{
+    if (B <= 0 || Hkv <= 0 || L < 1) return 0;
+    return (size_t)B * Hkv * kD * (size_t)((L + 63) / 64 * 64) * sizeof(minikv_f16);     // V transposed, keys padded to 64
+}
+
 int selective_flash_attn(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, const minikv_f16 *Q, const minikv_f16 *K,
                          const minikv_f16 *V, float sm_scale, minikv_f16 *X_O, float *lse, float *A_cumul,
-                         void *stream)
+                         void *workspace, size_t workspace_bytes, void *stream)
 {
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || L < 1 || L > ((int64_t)1 << 30)) return MINIKV_EINVAL;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(X_O) || !aligned16(lse)) return MINIKV_EINVAL;
     if (A_cumul && ((uintptr_t)A_cumul & 15u)) return MINIKV_EINVAL;
+    if (!aligned16(workspace)) return MINIKV_EINVAL;
     if (!(sm_scale == sm_scale) || sm_scale - sm_scale != 0.0f) return MINIKV_EINVAL;
-    if ((int64_t)B * Hq * ((L + 127) / 128) > 0x7fffffff) return MINIKV_EINVAL;     // one workgroup per row block
-    return launch_prefill(B, Hq, Hkv, L, Q, K, V, sm_scale, X_O, lse, A_cumul, (hipStream_t)stream);
+    if ((int64_t)B * Hq * ((L + 127) / 128) > 0x7fffffff || (int64_t)B * Hkv > 65535) return MINIKV_EINVAL;
+    if (workspace_bytes < selective_flash_attn_workspace_bytes(B, Hkv, L)) return MINIKV_EWORKSPACE;
+    return launch_prefill(B, Hq, Hkv, L, Q, K, V, sm_scale, X_O, lse, A_cumul, workspace, (hipStream_t)stream);
 }
 
 size_t kv_select_workspace_bytes(int32_t units, int32_t rep, int64_t L)

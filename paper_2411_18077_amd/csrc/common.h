@@ -79,7 +79,7 @@ int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache
 
 int launch_prefill(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, const minikv_f16 *Q, const minikv_f16 *K,
                    const minikv_f16 *V, float sm_scale, minikv_f16 *XO, float *lse, float *A_cumul,
-                   hipStream_t st);
+                   void *workspace, hipStream_t st);
 int launch_select(int32_t units, int32_t rep, int64_t L, const float *A, const int32_t *n_hh,
                   const int32_t *n_rw, int32_t *idx, int64_t idx_stride, int32_t *n_tok, void *workspace,
                   hipStream_t st);

@@ -10,7 +10,9 @@
 //                          tile), the rescale of the output is a per-lane multiply, and the fp32 scores, once
 //                          turned into fp16 weights, ARE the B operand of O^T = V^T P^T without any shuffle
 //                          (the key order inside a 16-key step is whatever the accumulator layout gives; the
-//                          V^T operand is read in the same order).  V is transposed on its way into LDS.
+//                          V^T operand is read in the same order).  V^T tiles come from a transposed copy of V
+//                          that prefill_vt_kernel writes once into the workspace: transposing inside the key
+//                          loop (2-byte LDS stores) cost as much as the rest of the loop together.
 //   prefill_colsum_kernel  column blocks in parallel.  A workgroup owns 128 keys (32 per wave, their K rows
 //                          held in registers as the B operand), walks the queries from the diagonal down in
 //                          tiles of 64 through LDS, recomputes S = Q K^T, normalises with the saved LSE and
@@ -33,6 +35,8 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 struct PrefillArgs {
     const _Float16 *Q, *K, *V;
+    _Float16 *Vt;                    // workspace: V transposed, [B*Hkv][128][Lp], zero beyond L
+    long Lp;                         // L rounded up to a multiple of 64
     _Float16 *XO;
     float *lse, *A_cumul;
     int Hq, rep, nblk;
@@ -73,16 +77,51 @@ __device__ __forceinline__ void store_tile_rowmajor(_Float16 *lds, const TileReg
         *(uint4 *)(lds + (chunk >> 4) * kPfKRow + (chunk & 15) * 8) = t.c[i];
     }
 }
-// The same chunks written transposed: lds[d][key].
-__device__ __forceinline__ void store_tile_transposed(_Float16 *lds, const TileRegs &t, int tid)
+// One tile of 128 channels x 64 keys of the transposed V: chunk = 8 keys of one channel.
+__device__ __forceinline__ TileRegs load_tile_vt(const _Float16 *vt, long Lp, long key0, int tid)
+{
+    TileRegs t;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int chunk = tid + 256 * i;                 // channel = chunk / 8, 8 keys at (chunk % 8) * 8
+        t.c[i] = *(const uint4 *)(vt + (long)(chunk >> 3) * Lp + key0 + (chunk & 7) * 8);
+    }
+    return t;
+}
+__device__ __forceinline__ void store_tile_vt(_Float16 *lds, const TileRegs &t, int tid)
 {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int chunk = tid + 256 * i;
-        const int key = chunk >> 4, d0 = (chunk & 15) * 8;
-        const half8 v = *(const half8 *)&t.c[i];
+        *(uint4 *)(lds + (chunk >> 3) * kPfVRow + (chunk & 7) * 8) = t.c[i];
+    }
+}
+
+// V [heads][L][128] -> Vt [heads][128][Lp], keys L .. Lp-1 zero (they meet zero weights, which must not meet NaN).
+__global__ __launch_bounds__(256) void prefill_vt_kernel(const _Float16 *__restrict__ V, _Float16 *__restrict__ Vt,
+                                                         long L, long Lp)
+{
+    __shared__ __align__(16) _Float16 tile[kPfN * kPfKRow];
+    const int tid = threadIdx.x;
+    const long head = blockIdx.y, key0 = (long)blockIdx.x * kPfN;
+    const _Float16 *vh = V + head * L * kPfD;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) lds[(d0 + j) * kPfVRow + key] = v[j];
+    for (int i = 0; i < 4; ++i) {
+        const int chunk = tid + 256 * i;
+        const long row = key0 + (chunk >> 4);
+        uint4 c = {0u, 0u, 0u, 0u};
+        if (row < L) c = *(const uint4 *)(vh + row * kPfD + (chunk & 15) * 8);
+        *(uint4 *)(tile + (chunk >> 4) * kPfKRow + (chunk & 15) * 8) = c;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int chunk = tid + 256 * i;
+        const int d = chunk >> 3, kc = (chunk & 7) * 8;
+        half8 v;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = tile[(kc + j) * kPfKRow + d];
+        *(half8 *)(Vt + (head * kPfD + d) * Lp + key0 + kc) = v;
     }
 }
 
@@ -98,7 +137,7 @@ __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
     const long bh = blockIdx.x % nbh;
     const long kvh = (bh / a.Hq) * (a.Hq / a.rep) + (bh % a.Hq) / a.rep;
     const long L = a.L;
-    const _Float16 *Qh = a.Q + bh * L * kPfD, *Kh = a.K + kvh * L * kPfD, *Vh = a.V + kvh * L * kPfD;
+    const _Float16 *Qh = a.Q + bh * L * kPfD, *Kh = a.K + kvh * L * kPfD, *Vth = a.Vt + kvh * kPfD * a.Lp;
 
     const long q0 = (long)qb * kPfM + wave * 32;       // first query of this wave
     const long query = q0 + r;                         // this lane's query column
@@ -116,15 +155,15 @@ __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
 
     const long kend = min((long)(qb + 1) * kPfM, L);   // keys 0 .. kend-1 are visible to some query of the block
     const int ntiles = (int)((kend + kPfN - 1) / kPfN);
-    TileRegs kr = load_tile(Kh, 0, L, tid), vr = load_tile(Vh, 0, L, tid);
+    TileRegs kr = load_tile(Kh, 0, L, tid), vr = load_tile_vt(Vth, a.Lp, 0, tid);
     for (int n = 0; n < ntiles; ++n) {
         __syncthreads();                               // every wave is done with the previous tile
         store_tile_rowmajor(Ks, kr, tid);
-        store_tile_transposed(Vt, vr, tid);
+        store_tile_vt(Vt, vr, tid);
         __syncthreads();
         if (n + 1 < ntiles) {
             kr = load_tile(Kh, (long)(n + 1) * kPfN, L, tid);
-            vr = load_tile(Vh, (long)(n + 1) * kPfN, L, tid);
+            vr = load_tile_vt(Vth, a.Lp, (long)(n + 1) * kPfN, tid);
         }
         const long key0 = (long)n * kPfN;
         if (key0 > q0 + 31) continue;                  // no query of this wave sees the tile (uniform in the wave)
@@ -271,14 +310,19 @@ __global__ __launch_bounds__(256, 2) void prefill_colsum_kernel(PrefillArgs a)
 
 int launch_prefill(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, const minikv_f16 *Q, const minikv_f16 *K,
                    const minikv_f16 *V, float sm_scale, minikv_f16 *XO, float *lse, float *A_cumul,
-                   hipStream_t st)
+                   void *workspace, hipStream_t st)
 {
     PrefillArgs a;
+    a.Lp = (L + kPfN - 1) / kPfN * kPfN;
+    a.Vt = (_Float16 *)workspace;
     a.Q = (const _Float16 *)Q, a.K = (const _Float16 *)K, a.V = (const _Float16 *)V;
     a.XO = (_Float16 *)XO, a.lse = lse, a.A_cumul = A_cumul;
     a.Hq = Hq, a.rep = Hq / Hkv, a.L = L, a.scale_log2 = sm_scale * kLog2e;
     a.nblk = (int)((L + kPfM - 1) / kPfM);
     const long blocks = (long)B * Hq * a.nblk;
+    hipLaunchKernelGGL(prefill_vt_kernel, dim3((unsigned)(a.Lp / kPfN), (unsigned)(B * Hkv)), dim3(256), 0, st, a.V,
+                       a.Vt, (long)L, a.Lp);
+    if (hipGetLastError() != hipSuccess) return MINIKV_ELAUNCH;
     hipLaunchKernelGGL(prefill_fwd_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
     if (hipGetLastError() != hipSuccess) return MINIKV_ELAUNCH;
     if (A_cumul) {

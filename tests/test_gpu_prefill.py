@@ -26,7 +26,9 @@ def run_gpu(Q, K, V, sm, want_cumul=True):
     xo = torch.full((B, Hq, L, D), float("nan"), dtype=torch.float16, device="cuda")
     lse = torch.full((B, Hq, L), float("nan"), dtype=torch.float32, device="cuda")
     acc = torch.full((B, Hq, L), float("nan"), dtype=torch.float32, device="cuda") if want_cumul else None
-    api.selective_flash_attn(B, Hq, K.shape[1], L, Q, K, V, sm, xo, lse, acc)
+    ws = torch.empty(api.selective_flash_attn_workspace_bytes(B, K.shape[1], L), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)                                           # no initial state needed (0xFFFF is an fp16 NaN)
+    api.selective_flash_attn(B, Hq, K.shape[1], L, Q, K, V, sm, xo, lse, acc, ws)
     torch.cuda.synchronize()
     return xo, lse, acc
 
