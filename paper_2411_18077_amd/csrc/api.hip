@@ -159,7 +159,7 @@ int selective_flash_attn(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, const mi
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(X_O) || !aligned16(lse)) return MINIKV_EINVAL;
     if (A_cumul && ((uintptr_t)A_cumul & 15u)) return MINIKV_EINVAL;
     if (!aligned16(workspace)) return MINIKV_EINVAL;
-    if (!(sm_scale == sm_scale) || sm_scale - sm_scale != 0.0f) return MINIKV_EINVAL;
+    if (!(sm_scale > 0.0f) || sm_scale - sm_scale != 0.0f) return MINIKV_EINVAL;       // positive and finite
     if ((int64_t)B * Hq * ((L + 127) / 128) > 0x7fffffff || (int64_t)B * Hkv > 65535) return MINIKV_EINVAL;
     if (workspace_bytes < selective_flash_attn_workspace_bytes(B, Hkv, L)) return MINIKV_EWORKSPACE;
     return launch_prefill(B, Hq, Hkv, L, Q, K, V, sm_scale, X_O, lse, A_cumul, workspace, (hipStream_t)stream);

@@ -30,6 +30,9 @@ constexpr int kPfM = 128;            // queries per workgroup (forward) / keys p
 constexpr int kPfN = 64;             // keys (forward) / queries (column sums) per LDS tile
 constexpr int kPfKRow = kPfD + 8;    // halves per row of a row-major tile in LDS (16-byte pad)
 constexpr int kPfVRow = kPfN + 8;    // halves per row of the transposed V tile in LDS
+constexpr int kPfKTile = kPfN * kPfKRow;   // halves of one row-major tile in LDS
+constexpr int kPfVTile = kPfD * kPfVRow;   // halves of one transposed V tile in LDS
+constexpr size_t kPfFwdLds = (size_t)2 * (kPfKTile + kPfVTile) * sizeof(_Float16);
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -127,8 +130,8 @@ __global__ __launch_bounds__(256) void prefill_vt_kernel(const _Float16 *__restr
 
 __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
 {
-    __shared__ __align__(16) _Float16 Ks[kPfN * kPfKRow];
-    __shared__ __align__(16) _Float16 Vt[kPfD * kPfVRow];
+    extern __shared__ __align__(16) _Float16 pf_lds[];
+    _Float16 *Ks = pf_lds, *Vt = pf_lds + 2 * kPfKTile;     // [2][64][136] and [2][128][72] halves
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, g = lane >> 5;
     // heaviest row blocks (the last ones: they see the most keys) first
@@ -155,79 +158,96 @@ __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
 
     const long kend = min((long)(qb + 1) * kPfM, L);   // keys 0 .. kend-1 are visible to some query of the block
     const int ntiles = (int)((kend + kPfN - 1) / kPfN);
+    const float c = a.scale_log2;                      // > 0: the running max is kept on the raw scores
+    // Two LDS buffers: tile n+1 is stored while tile n is computed on, one barrier per tile.
     TileRegs kr = load_tile(Kh, 0, L, tid), vr = load_tile_vt(Vth, a.Lp, 0, tid);
+    store_tile_rowmajor(Ks, kr, tid);
+    store_tile_vt(Vt, vr, tid);
+    if (ntiles > 1) {
+        kr = load_tile(Kh, kPfN, L, tid);
+        vr = load_tile_vt(Vth, a.Lp, kPfN, tid);
+    }
+    __syncthreads();
     for (int n = 0; n < ntiles; ++n) {
-        __syncthreads();                               // every wave is done with the previous tile
-        store_tile_rowmajor(Ks, kr, tid);
-        store_tile_vt(Vt, vr, tid);
-        __syncthreads();
-        if (n + 1 < ntiles) {
-            kr = load_tile(Kh, (long)(n + 1) * kPfN, L, tid);
-            vr = load_tile_vt(Vth, a.Lp, (long)(n + 1) * kPfN, tid);
+        const _Float16 *Kc = Ks + (n & 1) * kPfKTile, *Vc = Vt + (n & 1) * kPfVTile;
+        if (n + 1 < ntiles) {                          // the other buffer was last read before the previous barrier
+            store_tile_rowmajor(Ks + ((n + 1) & 1) * kPfKTile, kr, tid);
+            store_tile_vt(Vt + ((n + 1) & 1) * kPfVTile, vr, tid);
+        }
+        if (n + 2 < ntiles) {
+            kr = load_tile(Kh, (long)(n + 2) * kPfN, L, tid);
+            vr = load_tile_vt(Vth, a.Lp, (long)(n + 2) * kPfN, tid);
         }
         const long key0 = (long)n * kPfN;
-        if (key0 > q0 + 31) continue;                  // no query of this wave sees the tile (uniform in the wave)
-
-        float16v s[2];
+        if (key0 <= q0 + 31) {                         // else no query of this wave sees the tile (uniform in the wave)
+            float16v s[2];
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+            for (int t = 0; t < 2; ++t) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) s[t][i] = 0.0f;
+                for (int i = 0; i < 16; ++i) s[t][i] = 0.0f;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const half8 kf = *(const half8 *)(Ks + (t * 32 + r) * kPfKRow + ks * 16 + g * 8);
-                s[t] = mfma32(kf, qf[ks], s[t]);
-            }
-        }
-        const bool diag = key0 + kPfN - 1 > q0;        // some (key, query) pair of the tile is above the diagonal
-        float mx = m;
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float v = s[t][i] * a.scale_log2;
-                if (diag && key0 + t * 32 + acc_row(i, g) > query) v = -INFINITY;
-                s[t][i] = v;
-                mx = fmaxf(mx, v);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));        // the other half-wave holds the other 32 keys of the column
-        const float alpha = __builtin_amdgcn_exp2f(m - mx);             // m = -inf at the first tile: alpha = 0, nothing to rescale
-        m = mx;
-        float psum = 0.0f;
-        half8 pb[2][2];                                // B operands of O^T += V^T P^T, 16 keys each
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float p = __builtin_amdgcn_exp2f(s[t][i] - mx);
-                psum += p;
-                pb[t][i >> 3][i & 7] = (_Float16)p;
-            }
-        l = l * alpha + psum;
-        if (__any(alpha != 1.0f)) {
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-        }
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int sx = 0; sx < 2; ++sx)
-#pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    // keys of this step in accumulator order: 32 t + 16 sx + 4 g + {0..3} and the same + 8
-                    const _Float16 *vp = Vt + (db * 32 + r) * kPfVRow + t * 32 + sx * 16 + g * 4;
-                    const half4 lo = *(const half4 *)vp, hi = *(const half4 *)(vp + 8);
-                    const half8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    o[db] = mfma32(vf, pb[t][sx], o[db]);
+                for (int ks = 0; ks < 8; ++ks) {
+                    const half8 kf = *(const half8 *)(Kc + (t * 32 + r) * kPfKRow + ks * 16 + g * 8);
+                    s[t] = mfma32(kf, qf[ks], s[t]);
                 }
+            }
+            float mx = m;
+            if (key0 + kPfN - 1 > q0) {                // the diagonal crosses the tile: keys after the query are masked
+                const int rel = (int)(query - key0);   // keys at tile offsets 0 .. rel are visible to this lane
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        if (t * 32 + acc_row(i, g) > rel) s[t][i] = -INFINITY;
+                        mx = fmaxf(mx, s[t][i]);
+                    }
+            } else {
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[t][i]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));    // the other half-wave holds the other 32 keys of the column
+            const float alpha = __builtin_amdgcn_exp2f((m - mx) * c);   // m = -inf at the first tile: alpha = 0
+            m = mx;
+            const float mc = -mx * c;
+            float psum = 0.0f;
+            half8 pb[2][2];                            // B operands of O^T += V^T P^T, 16 keys each
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][i], c, mc));
+                    psum += p;
+                    pb[t][i >> 3][i & 7] = (_Float16)p;
+                }
+            l = l * alpha + psum;
+            if (__any(alpha != 1.0f)) {
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int sx = 0; sx < 2; ++sx)
+#pragma unroll
+                    for (int db = 0; db < 4; ++db) {
+                        // keys of this step in accumulator order: 32 t + 16 sx + 4 g + {0..3} and the same + 8
+                        const _Float16 *vp = Vc + (db * 32 + r) * kPfVRow + t * 32 + sx * 16 + g * 4;
+                        const half4 lo = *(const half4 *)vp, hi = *(const half4 *)(vp + 8);
+                        const half8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        o[db] = mfma32(vf, pb[t][sx], o[db]);
+                    }
+        }
+        __syncthreads();                               // tile n+1 is in place, everyone is done with tile n
     }
 
     l += __shfl_xor(l, 32, 64);
     const float inv = 1.0f / l;
     if (query < L) {
-        if (g == 0) a.lse[bh * L + query] = (m + log2f(l)) * kLn2;
+        if (g == 0) a.lse[bh * L + query] = (m * c + log2f(l)) * kLn2;
         _Float16 *orow = a.XO + (bh * L + query) * kPfD;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
@@ -243,8 +263,8 @@ __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
 
 __global__ __launch_bounds__(256, 2) void prefill_colsum_kernel(PrefillArgs a)
 {
-    __shared__ __align__(16) _Float16 Qs[kPfN * kPfKRow];
-    __shared__ __align__(16) float lse2[kPfN];         // LSE of the tile's queries, in powers of two
+    __shared__ __align__(16) _Float16 Qs[2 * kPfKTile];
+    __shared__ __align__(16) float lse2[2 * kPfN];     // LSE of the tile's queries, in powers of two (two buffers each)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, g = lane >> 5;
     // column blocks in natural order: block 0 is seen by every query and is the heaviest
@@ -264,45 +284,61 @@ __global__ __launch_bounds__(256, 2) void prefill_colsum_kernel(PrefillArgs a)
     for (int ks = 0; ks < 8; ++ks) kf[ks] = *(const half8 *)(Kh + krow * kPfD + ks * 16 + g * 8);
 
     float colsum = 0.0f;
+    const float c = a.scale_log2;
     const int tile0 = (int)(((long)kb * kPfM) / kPfN), ntiles = (int)((L + kPfN - 1) / kPfN);
     TileRegs qr = load_tile(Qh, (long)tile0 * kPfN, L, tid);
     float lr = 0.0f;
     if (tid < kPfN) lr = lseh[min((long)tile0 * kPfN + tid, L - 1)];
+    store_tile_rowmajor(Qs, qr, tid);
+    if (tid < kPfN) lse2[tid] = lr * kLog2e;
+    if (tile0 + 1 < ntiles) {
+        qr = load_tile(Qh, (long)(tile0 + 1) * kPfN, L, tid);
+        if (tid < kPfN) lr = lseh[min((long)(tile0 + 1) * kPfN + tid, L - 1)];
+    }
+    __syncthreads();
     for (int n = tile0; n < ntiles; ++n) {
-        __syncthreads();
-        store_tile_rowmajor(Qs, qr, tid);
-        if (tid < kPfN) lse2[tid] = lr * kLog2e;
-        __syncthreads();
+        const int cur = (n - tile0) & 1;
+        const _Float16 *Qc = Qs + cur * kPfKTile;
+        const float *lc = lse2 + cur * kPfN;
         if (n + 1 < ntiles) {
-            qr = load_tile(Qh, (long)(n + 1) * kPfN, L, tid);
-            if (tid < kPfN) lr = lseh[min((long)(n + 1) * kPfN + tid, L - 1)];
+            store_tile_rowmajor(Qs + (cur ^ 1) * kPfKTile, qr, tid);
+            if (tid < kPfN) lse2[(cur ^ 1) * kPfN + tid] = lr * kLog2e;
+        }
+        if (n + 2 < ntiles) {
+            qr = load_tile(Qh, (long)(n + 2) * kPfN, L, tid);
+            if (tid < kPfN) lr = lseh[min((long)(n + 2) * kPfN + tid, L - 1)];
         }
         const long qt0 = (long)n * kPfN;
-        if (qt0 + kPfN - 1 < k0) continue;             // every query of the tile precedes every key of this wave
-        const bool edge = qt0 < k0 + 31 || qt0 + kPfN > L;   // the diagonal or the end of the prompt crosses the tile
+        if (qt0 + kPfN - 1 >= k0) {                    // else every query of the tile precedes every key of this wave
+            const bool edge = qt0 < k0 + 31 || qt0 + kPfN > L;   // the diagonal or the end of the prompt crosses the tile
+            const int lo_q = (int)(key - qt0), hi_q = (int)min(L - qt0, (long)kPfN);   // tile rows lo_q .. hi_q-1 count
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            float16v s;
+            for (int t = 0; t < 2; ++t) {
+                float16v s;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) s[i] = 0.0f;
+                for (int i = 0; i < 16; ++i) s[i] = 0.0f;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const half8 qf = *(const half8 *)(Qs + (t * 32 + r) * kPfKRow + ks * 16 + g * 8);
-                s = mfma32(qf, kf[ks], s);
-            }
+                for (int ks = 0; ks < 8; ++ks) {
+                    const half8 qf = *(const half8 *)(Qc + (t * 32 + r) * kPfKRow + ks * 16 + g * 8);
+                    s = mfma32(qf, kf[ks], s);
+                }
 #pragma unroll
-            for (int iq = 0; iq < 4; ++iq) {
-                const float4 ls = *(const float4 *)&lse2[t * 32 + iq * 8 + g * 4];
-                const float lsv[4] = {ls.x, ls.y, ls.z, ls.w};
+                for (int iq = 0; iq < 4; ++iq) {
+                    const float4 ls = *(const float4 *)&lc[t * 32 + iq * 8 + g * 4];
+                    const float lsv[4] = {ls.x, ls.y, ls.z, ls.w};
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const long q = qt0 + t * 32 + iq * 8 + g * 4 + j;
-                    float p = __builtin_amdgcn_exp2f(s[iq * 4 + j] * a.scale_log2 - lsv[j]);
-                    if (edge && (q < key || q >= L)) p = 0.0f;
-                    colsum += p;
+                    for (int j = 0; j < 4; ++j) {
+                        float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[iq * 4 + j], c, -lsv[j]));
+                        if (edge) {
+                            const int row = t * 32 + iq * 8 + g * 4 + j;
+                            if (row < lo_q || row >= hi_q) p = 0.0f;
+                        }
+                        colsum += p;
+                    }
                 }
             }
         }
+        __syncthreads();
     }
     colsum += __shfl_xor(colsum, 32, 64);
     if (g == 0 && key < L) a.A_cumul[bh * L + key] = colsum;
@@ -323,7 +359,10 @@ int launch_prefill(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, const minikv_f
     hipLaunchKernelGGL(prefill_vt_kernel, dim3((unsigned)(a.Lp / kPfN), (unsigned)(B * Hkv)), dim3(256), 0, st, a.V,
                        a.Vt, (long)L, a.Lp);
     if (hipGetLastError() != hipSuccess) return MINIKV_ELAUNCH;
-    hipLaunchKernelGGL(prefill_fwd_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
+    if (hipFuncSetAttribute((const void *)prefill_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)kPfFwdLds) != hipSuccess)
+        return MINIKV_ELAUNCH;
+    hipLaunchKernelGGL(prefill_fwd_kernel, dim3((unsigned)blocks), dim3(256), kPfFwdLds, st, a);
     if (hipGetLastError() != hipSuccess) return MINIKV_ELAUNCH;
     if (A_cumul) {
         hipLaunchKernelGGL(prefill_colsum_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
