@@ -270,9 +270,10 @@ def main():
         # holds, half of them heavy hitters and half recent window, from synthetic cumulative attention scores
         rep = w.Hq // w.Hkv
         A = W.make_scores(w.units * rep, w.L, seed=w.seed + 5, device="cuda", kind="attention")
-        n_hh = (inp.n_tok // 2 // w.G * w.G).to(torch.int32)
-        n_rw = (inp.n_tok - n_hh).to(torch.int32)
-        stride = int(inp.n_tok.max())
+        kept = copies[0]["n_tok"]
+        n_hh = (kept // 2 // w.G * w.G).to(torch.int32)
+        n_rw = (kept - n_hh).to(torch.int32)
+        stride = int(kept.max())
         sel_idx = torch.empty(w.units, stride, dtype=torch.int32, device="cuda")
         sel_n = torch.empty(w.units, dtype=torch.int32, device="cuda")
         nws = api.kv_select_workspace_bytes(w.units, rep, w.L)
@@ -290,6 +291,30 @@ def main():
             "what": "kv_select_hh_rw on this shape (sum of the group's query heads, top n_hh by score + recent "
                     "window, ascending positions), mean of %d back-to-back calls" % reps,
             "us": round(sel_us, 2), "bytes": sel_bytes, "GB/s": round(sel_bytes / sel_us / 1e3, 1),
+        }
+        # prefill attention with cumulative scores (both passes), one sequence with this workload's heads and
+        # context, and the longest prompt of the paper's kernel table (8192 tokens, 32 heads)
+        def time_prefill(Bp, Hq, Hkv, Lp, reps):
+            Qp, Kp, Vp = W.make_prefill_inputs(Bp, Hq, Hkv, Lp, w.seed + 9, device="cuda")
+            xo = torch.empty_like(Qp)
+            lse = torch.empty(Bp, Hq, Lp, dtype=torch.float32, device="cuda")
+            acc = torch.empty(Bp, Hq, Lp, dtype=torch.float32, device="cuda")
+            pws = torch.empty(api.selective_flash_attn_workspace_bytes(Bp, Hkv, Lp), dtype=torch.uint8, device="cuda")
+            for i in range(1 + reps):
+                if i == 1:
+                    a.record()
+                api.selective_flash_attn(Bp, Hq, Hkv, Lp, Qp, Kp, Vp, 1.0 / math.sqrt(w.D), xo, lse, acc, pws)
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / reps
+            fl = W.prefill_flops(Bp, Hq, Lp)
+            return {"B": Bp, "Hq": Hq, "Hkv": Hkv, "L": Lp, "ms": round(ms, 3), "TFLOP/s": round(fl / ms / 1e9, 1),
+                    "frac_of_fp16_mfma_peak": round(fl / ms / 1e9 / 2500.0, 3)}
+        result["selective_flash_attn"] = {
+            "what": "selective_flash_attn (X_O, LSE and A_cumul: transpose of V + row-block pass + column-block pass); "
+                    "flops = 6*D per causal (query, key) pair; peak 2500 TFLOP/s (dense fp16 matrix instructions)",
+            "this_shape": time_prefill(1, w.Hq, w.Hkv, w.L, 3),
+            "paper_table_longest": time_prefill(1, 32, 32, 8192, 10),
         }
         result["build_s"] = round(t_build, 1)
 
