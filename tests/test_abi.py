@@ -25,7 +25,8 @@ def test_exports_every_declared_symbol(api):
     names = sorted(set(names))
     assert {"kv_quantize_pack", "kv_append_residual", "kv_flush_residual", "minikv_decode_attn",
             "minikv_workspace_bytes", "minikv_buffer_bytes", "minikv_abi_version", "kv_select_hh_rw",
-            "kv_select_workspace_bytes", "kv_pyramid_budget"} <= set(names)
+            "kv_select_workspace_bytes", "kv_pyramid_budget", "selective_flash_attn",
+            "selective_flash_attn_workspace_bytes"} <= set(names)
     l = api.lib()
     for n in names:
         assert hasattr(l, n), n
@@ -111,3 +112,22 @@ def test_pyramid_budget_is_host_arithmetic_and_matches_the_oracle(api):
     for bad in [(0, 1.0, 7, 1), (4, -1.0, 7, 1), (4, float("nan"), 7, 1), (4, 1.0, 0, 1)]:
         with pytest.raises(api.MinikvError):
             api.kv_pyramid_budget(*bad)
+
+
+def test_prefill_arguments_are_checked_on_the_host(api):
+    l, P = api.lib(), C.c_void_p
+    p = P(0x1000)
+    nws = api.selective_flash_attn_workspace_bytes(2, 2, 100)
+    assert nws == 2 * 2 * 128 * 128 * 2                      # V transposed, 100 keys padded to 128
+    assert api.selective_flash_attn_workspace_bytes(0, 2, 100) == 0
+    call = lambda B, Hq, Hkv, L, sm, ws=p, wsb=nws, Q=p, acc=p: l.selective_flash_attn(
+        B, Hq, Hkv, L, Q, p, p, sm, p, p, acc, ws, wsb, None)
+    assert call(0, 4, 2, 100, 0.1) == -1
+    assert call(2, 5, 2, 100, 0.1) == -1                     # Hq not a multiple of Hkv
+    assert call(2, 4, 2, 0, 0.1) == -1                       # empty prompt
+    assert call(2, 4, 2, 100, 0.0) == -1 and call(2, 4, 2, 100, -1.0) == -1      # scale must be positive
+    assert call(2, 4, 2, 100, float("nan")) == -1 and call(2, 4, 2, 100, float("inf")) == -1
+    assert call(2, 4, 2, 100, 0.1, Q=P(0x1008)) == -1        # misaligned
+    assert call(2, 4, 2, 100, 0.1, acc=P(0x1004)) == -1
+    assert call(2, 4, 2, 100, 0.1, ws=None) == -1
+    assert call(2, 4, 2, 100, 0.1, wsb=nws - 1) == -3
