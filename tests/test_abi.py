@@ -21,7 +21,7 @@ def api():
 def test_exports_every_declared_symbol(api):
     text = open(os.path.join(ROOT, "include", "minikv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b(minikv_\w+|kv_\w+)\s*\(", text)
+    names = re.findall(r"\b(minikv_\w+|kv_\w+|selective_flash_attn\w*)\s*\(", text)
     names = sorted(set(names))
     assert {"kv_quantize_pack", "kv_append_residual", "kv_flush_residual", "minikv_decode_attn",
             "minikv_workspace_bytes", "minikv_buffer_bytes", "minikv_abi_version", "kv_select_hh_rw",
