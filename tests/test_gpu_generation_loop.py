@@ -113,6 +113,59 @@ def test_one_step_captured_in_a_graph_and_replayed(g):
     g.assert_cache_bit_exact(gc, rc, what=("Kc", "Ks", "Kz", "Vc", "Vs", "Vz"))
 
 
+def test_generation_of_1024_tokens_replaying_one_captured_step(g):
+    """The paper's generation length (1024 new tokens): one captured step (append, flush, attend) replayed
+    1024 times on a small shape with G = 16 and n_r = 64, i.e. 16 flushes; the oracle follows every step
+    (its state must match at the end, bit for bit) and its attention output is compared on every 7th step
+    and around every flush."""
+    from paper_2411_18077_amd import api
+    from oracle import ref
+    steps = 1024
+    w = small(G=16, B=1, Hq=4, Hkv=2, L=256, Rcap=64, seed=314)
+    inp = W.make_inputs(w, "cuda")
+    Tcap = 128 + steps + 128                                # kept prompt tokens + everything generated, in tiles of 128
+    s, rs = g.shapes_for(w, Tcap)
+    gc = g.gpu_build_cache(inp, s)
+    rc = g.ref_build_cache(inp, rs)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(8)
+    ks = torch.randn(steps, w.units, w.D, generator=gen, device="cuda").to(torch.float16)
+    vs = torch.randn(steps, w.units, w.D, generator=gen, device="cuda").to(torch.float16)
+    qs = torch.randn(steps, w.B, w.Hq, w.D, generator=gen, device="cuda").to(torch.float16)
+    ks_h, vs_h, qs_h = g.to_np(ks), g.to_np(vs), g.to_np(qs)
+    k = torch.zeros(w.units, w.D, dtype=torch.float16, device="cuda"); v = torch.zeros_like(k)
+    q = torch.zeros(w.B, w.Hq, w.D, dtype=torch.float16, device="cuda"); out = torch.zeros_like(q)
+    ws = gc.workspace
+    side = torch.cuda.Stream(); side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+
+    def step_eager():
+        api.kv_append_residual(s, k, v, gc); api.kv_flush_residual(s, gc)
+        api.minikv_decode_attn(s, q, gc, g.sm_scale(), out, workspace=ws)
+
+    k.copy_(ks[0]); v.copy_(vs[0]); q.copy_(qs[0])
+    step_eager()                                            # step 0 eagerly (warm-up), then capture
+    torch.cuda.synchronize()
+    assert ref.append_residual(rc, ks_h[0], vs_h[0]) == 0 and ref.flush_residual(rc) == 0
+    with torch.cuda.graph(graph, stream=side):
+        step_eager()
+    worst, checked = 0.0, 0
+    for i in range(1, steps):
+        k.copy_(ks[i]); v.copy_(vs[i]); q.copy_(qs[i])
+        graph.replay()
+        assert ref.append_residual(rc, ks_h[i], vs_h[i]) == 0 and ref.flush_residual(rc) == 0
+        if i % 7 == 0 or (i + 1) % w.Rcap <= 1:
+            torch.cuda.synchronize()
+            want, _, _ = ref.decode_attn(rc, qs_h[i], g.sm_scale())
+            worst = max(worst, float(np.max(np.abs(g.to_np(out).astype(np.float64) - want))))
+            checked += 1
+            assert worst <= TOL, "step %d" % i
+    torch.cuda.synchronize()
+    assert checked > 150
+    assert gc.q_len.cpu().tolist() == rc.q_len.tolist() == [128 + steps // w.Rcap * w.Rcap] * w.units
+    assert gc.r_len.cpu().tolist() == rc.r_len.tolist()
+    g.assert_cache_bit_exact(gc, rc, what=("Kc", "Ks", "Kz", "Vc", "Vs", "Vz"))
+
+
 @pytest.mark.parametrize("L,Hq", [(32768, 4), (262144, 4), (262144, 8)])
 def test_one_unit_served_by_many_waves(g, L, Hq):
     """A single (batch, KV head) with a very long cache: hundreds of waves share the unit, so the split-K
