@@ -29,7 +29,8 @@ constexpr int kPfD = 128;            // head dimension
 constexpr int kPfM = 128;            // queries per workgroup (forward) / keys per workgroup (column sums)
 constexpr int kPfN = 64;             // keys (forward) / queries (column sums) per LDS tile
 constexpr int kPfKRow = kPfD + 8;    // halves per row of a row-major tile in LDS (16-byte pad)
-constexpr int kPfVRow = kPfN + 8;    // halves per row of the transposed V tile in LDS
+constexpr int kPfVRow = kPfN + 4;    // halves per row of the transposed V tile in LDS: 34 words, so that the 64-bit
+                                     // fragment reads of 32 consecutive rows fall on 32 different bank pairs
 constexpr int kPfKTile = kPfN * kPfKRow;   // halves of one row-major tile in LDS
 constexpr int kPfVTile = kPfD * kPfVRow;   // halves of one transposed V tile in LDS
 constexpr size_t kPfFwdLds = (size_t)2 * (kPfKTile + kPfVTile) * sizeof(_Float16);
@@ -96,7 +97,9 @@ __device__ __forceinline__ void store_tile_vt(_Float16 *lds, const TileRegs &t, 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int chunk = tid + 256 * i;
-        *(uint4 *)(lds + (chunk >> 3) * kPfVRow + (chunk & 7) * 8) = t.c[i];
+        uint2 *p = (uint2 *)(lds + (chunk >> 3) * kPfVRow + (chunk & 7) * 8);       // rows are 8-byte aligned only
+        p[0] = make_uint2(t.c[i].x, t.c[i].y);
+        p[1] = make_uint2(t.c[i].z, t.c[i].w);
     }
 }
 
@@ -131,7 +134,7 @@ __global__ __launch_bounds__(256) void prefill_vt_kernel(const _Float16 *__restr
 __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
 {
     extern __shared__ __align__(16) _Float16 pf_lds[];
-    _Float16 *Ks = pf_lds, *Vt = pf_lds + 2 * kPfKTile;     // [2][64][136] and [2][128][72] halves
+    _Float16 *Ks = pf_lds, *Vt = pf_lds + 2 * kPfKTile;     // [2][64][136] and [2][128][68] halves
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 31, g = lane >> 5;
     // heaviest row blocks (the last ones: they see the most keys) first
