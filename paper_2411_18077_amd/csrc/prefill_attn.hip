@@ -34,6 +34,7 @@ constexpr int kPfVRow = kPfN + 4;    // halves per row of the transposed V tile 
 constexpr int kPfKTile = kPfN * kPfKRow;   // halves of one row-major tile in LDS
 constexpr int kPfVTile = kPfD * kPfVRow;   // halves of one transposed V tile in LDS
 constexpr size_t kPfFwdLds = (size_t)2 * (kPfKTile + kPfVTile) * sizeof(_Float16);
+constexpr int kWaitVm0 = 0x0F70;      // s_waitcnt vmcnt(0), other counters untouched
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -166,6 +167,10 @@ __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
     TileRegs kr = load_tile(Kh, 0, L, tid), vr = load_tile_vt(Vth, a.Lp, 0, tid);
     store_tile_rowmajor(Ks, kr, tid);
     store_tile_vt(Vt, vr, tid);
+    // Every load so far (the Q rows among them) has returned by now, since loads return in order and the stores
+    // above needed the last ones.  Saying so keeps the compiler from guarding the Q registers inside the loop
+    // with counts that would also wait for the prefetch issued just before.
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
     if (ntiles > 1) {
         kr = load_tile(Kh, kPfN, L, tid);
         vr = load_tile_vt(Vth, a.Lp, kPfN, tid);
@@ -294,6 +299,7 @@ __global__ __launch_bounds__(256, 2) void prefill_colsum_kernel(PrefillArgs a)
     if (tid < kPfN) lr = lseh[min((long)tile0 * kPfN + tid, L - 1)];
     store_tile_rowmajor(Qs, qr, tid);
     if (tid < kPfN) lse2[tid] = lr * kLog2e;
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);              // as in the first pass: the K rows have arrived
     if (tile0 + 1 < ntiles) {
         qr = load_tile(Qh, (long)(tile0 + 1) * kPfN, L, tid);
         if (tid < kPfN) lr = lseh[min((long)(tile0 + 1) * kPfN + tid, L - 1)];
