@@ -187,7 +187,7 @@ def main():
         "dtype": "f16",
         "data": "synthetic",
         "config": {
-            "workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "context": w.L,
+            "workload": w.name, "seed": "%d + 7919 per cache copy" % w.seed, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "context": w.L,
             "retained_per_unit": int(max(q_len)) if w.keep is not None else "ragged %d..%d" % (min(q_len), max(q_len)),
             "G": w.G, "residual": w.Rcap, "Tcap": int(shape.Tcap), "cache_copies": ncopy,
             "algorithmic_bytes_per_step": alg_bytes, "variant": args.variant,
@@ -266,6 +266,24 @@ def main():
         torch.cuda.synchronize()
         result["flush_residual"] = {"ms": round(a.elapsed_time(b), 4), "tokens_per_unit": w.Rcap,
                                     "amortised_us_per_step": round(a.elapsed_time(b) * 1e3 / w.Rcap, 3)}
+        # reference point: a plain streaming read of 4 GiB (far beyond the 256 MB Infinity Cache), best of 5
+        probe_src = torch.empty(1 << 30, dtype=torch.int32, device=dev).fill_(1)
+        probe_sums = torch.zeros(2048, dtype=torch.int32, device=dev)
+        best = 1e9
+        for i in range(6):
+            a.record()
+            api.minikv_stream_read_probe(probe_src, probe_sums)
+            b.record()
+            torch.cuda.synchronize()
+            if i:
+                best = min(best, a.elapsed_time(b))
+        ceiling = probe_src.numel() * 4 / (best * 1e-3) / 1e9
+        del probe_src
+        result["streaming_read_ceiling"] = {
+            "what": "plain 128-bit streaming read of 4 GiB (minikv_stream_read_probe), best of 5",
+            "GB/s": round(ceiling, 1),
+            "decode_kernel_pct_of_it": round(100.0 * result["roofline"]["achieved"] / ceiling, 1),
+        }
         # prefill-side token selection on this workload's shape: each unit keeps as many tokens as its cache
         # holds, half of them heavy hitters and half recent window, from synthetic cumulative attention scores
         rep = w.Hq // w.Hkv

@@ -183,6 +183,11 @@ int kv_select_hh_rw(int32_t units, int32_t rep, int64_t L, const float *A_cumul,
  * Returns MINIKV_EINVAL for n_layers < 1, d < 1, x < 0 or NaN, or a null pointer. */
 int kv_pyramid_budget(int32_t n_layers, double x, int32_t d, int32_t bottom_heavy, double *budget);
 
+/* Diagnostics: a plain streaming read (128-bit loads, 2048 workgroups) of `bytes` bytes (rounded down to 16) at
+ * src, the reference point the bandwidth figures are compared with.  sums: uint32 [2048] (device), xor-updated
+ * with a checksum per workgroup. */
+int minikv_stream_read_probe(const void *src, size_t bytes, uint32_t *sums, void *stream);
+
 /* Diagnostics: selects the kernel variant minikv_decode_attn launches (process-wide).
  *   0 = default (fastest verified), 1 = plain scalar-loop kernel kept for cross-checks,
  *   others as listed by minikv_strvariant().  Returns MINIKV_EINVAL for an unknown id. */

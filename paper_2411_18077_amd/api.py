@@ -70,6 +70,8 @@ def lib():
                                            C.c_size_t, P]
         l.selective_flash_attn_workspace_bytes.restype = C.c_size_t
         l.selective_flash_attn_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int64]
+        l.minikv_stream_read_probe.restype = C.c_int
+        l.minikv_stream_read_probe.argtypes = [P, C.c_size_t, P, P]
         l.kv_select_workspace_bytes.restype = C.c_size_t
         l.kv_select_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int64]
         l.kv_select_hh_rw.restype = C.c_int
@@ -183,6 +185,11 @@ def kv_pyramid_budget(n_layers, x, d, bottom_heavy):
     out = (C.c_double * max(int(n_layers), 1))()
     _check(lib().kv_pyramid_budget(int(n_layers), float(x), int(d), int(bottom_heavy), out), "kv_pyramid_budget")
     return list(out)[: int(n_layers)]
+
+
+def minikv_stream_read_probe(src, sums, stream=None):
+    _check(lib().minikv_stream_read_probe(_ptr(src), src.numel() * src.element_size(), _ptr(sums), _stream(stream)),
+           "minikv_stream_read_probe")
 
 
 def minikv_set_variant(v):

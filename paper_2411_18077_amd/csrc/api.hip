@@ -46,6 +46,27 @@ static int validate_cache(const minikv_shape &s, const minikv_cache *c)
     return MINIKV_OK;
 }
 
+// Reference point for the bandwidth figures: reads a buffer once with 128-bit loads, 2048 workgroups striding
+// through it, and folds it into one word per workgroup (so that the loads cannot be dropped).
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ src, size_t n16,
+                                                         uint32_t *__restrict__ sums)
+{
+    uint32_t acc = 0;
+    const size_t stride = (size_t)gridDim.x * 256 * 8;
+    for (size_t i = (size_t)blockIdx.x * 256 * 8 + threadIdx.x; i < n16; i += stride) {
+        uint4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const size_t k = i + (size_t)j * 256;
+            v[j] = src[k < n16 ? k : n16 - 1];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+    }
+    for (int d = 32; d >= 1; d >>= 1) acc ^= __shfl_xor(acc, d, 64);
+    if ((threadIdx.x & 63) == 0) atomicXor(&sums[blockIdx.x], acc);
+}
+
 }  // namespace minikv
 
 using namespace minikv;
@@ -194,6 +215,14 @@ int kv_pyramid_budget(int32_t n_layers, double x, int32_t d, int32_t bottom_heav
     for (int32_t l = 0; l < n_layers; ++l)
         budget[l] = n_layers == 1 ? x : first + (last - first) * l / (n_layers - 1);
     return MINIKV_OK;
+}
+
+int minikv_stream_read_probe(const void *src, size_t bytes, uint32_t *sums, void *stream)
+{
+    if (!aligned16(src) || !sums || ((uintptr_t)sums & 3u) || bytes < 16) return MINIKV_EINVAL;
+    hipLaunchKernelGGL(stream_read_kernel, dim3(2048), dim3(256), 0, (hipStream_t)stream, (const uint4 *)src,
+                       bytes / 16, sums);
+    return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
 }
 
 int minikv_set_variant(int variant)
