@@ -171,9 +171,6 @@ __device__ inline float ld_agent(const float *p)
 }
 __device__ inline float2 ld_agent2(const float *p)      // two consecutive floats, p 8-byte aligned
 {
-#ifdef MINIKV_PLAIN_MERGE_LOADS
-    return *reinterpret_cast<const float2 *>(p);
-#endif
     const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
                                                    __HIP_MEMORY_SCOPE_AGENT);
     return float2{__builtin_bit_cast(float, (uint32_t)v), __builtin_bit_cast(float, (uint32_t)(v >> 32))};
