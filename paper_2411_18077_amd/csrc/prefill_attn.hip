@@ -163,41 +163,43 @@ __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
     const long kend = min((long)(qb + 1) * kPfM, L);   // keys 0 .. kend-1 are visible to some query of the block
     const int ntiles = (int)((kend + kPfN - 1) / kPfN);
     const float c = a.scale_log2;                      // > 0: the running max is kept on the raw scores
-    // Two LDS buffers: tile n+1 is stored while tile n is computed on, one barrier per tile.
+    // Two LDS buffers, one barrier per tile.  The global loads of tile n+1 are issued after the score products
+    // of tile n (whose K fragments can then use those registers) and stored to the other buffer at the end of
+    // the iteration, behind the softmax and the output products.
     TileRegs kr = load_tile(Kh, 0, L, tid), vr = load_tile_vt(Vth, a.Lp, 0, tid);
     store_tile_rowmajor(Ks, kr, tid);
     store_tile_vt(Vt, vr, tid);
     // Every load so far (the Q rows among them) has returned by now, since loads return in order and the stores
     // above needed the last ones.  Saying so keeps the compiler from guarding the Q registers inside the loop
-    // with counts that would also wait for the prefetch issued just before.
+    // with counts that would also wait for the prefetch.
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
-    if (ntiles > 1) {
-        kr = load_tile(Kh, kPfN, L, tid);
-        vr = load_tile_vt(Vth, a.Lp, kPfN, tid);
-    }
     __syncthreads();
     for (int n = 0; n < ntiles; ++n) {
         const _Float16 *Kc = Ks + (n & 1) * kPfKTile, *Vc = Vt + (n & 1) * kPfVTile;
-        if (n + 1 < ntiles) {                          // the other buffer was last read before the previous barrier
-            store_tile_rowmajor(Ks + ((n + 1) & 1) * kPfKTile, kr, tid);
-            store_tile_vt(Vt + ((n + 1) & 1) * kPfVTile, vr, tid);
-        }
-        if (n + 2 < ntiles) {
-            kr = load_tile(Kh, (long)(n + 2) * kPfN, L, tid);
-            vr = load_tile_vt(Vth, a.Lp, (long)(n + 2) * kPfN, tid);
-        }
         const long key0 = (long)n * kPfN;
         if (key0 <= q0 + 31) {                         // else no query of this wave sees the tile (uniform in the wave)
+            // all 8 K fragments of the first 32 keys are requested before the first product; each is replaced
+            // by the fragment of the second 32 keys as soon as it is consumed
             float16v s[2];
+            half8 kf[8];
+            const _Float16 *kp = Kc + r * kPfKRow + g * 8;
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
+            for (int ks = 0; ks < 8; ++ks) kf[ks] = *(const half8 *)(kp + ks * 16);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) s[t][i] = 0.0f;
+            for (int i = 0; i < 16; ++i) s[0][i] = 0.0f, s[1][i] = 0.0f;
+            __builtin_amdgcn_sched_barrier(0);         // keep the requests above the products (the scheduler would
+                                                       // otherwise pull each one down to its use to save registers)
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    const half8 kf = *(const half8 *)(Kc + (t * 32 + r) * kPfKRow + ks * 16 + g * 8);
-                    s[t] = mfma32(kf, qf[ks], s[t]);
-                }
+            for (int ks = 0; ks < 8; ++ks) {
+                s[0] = mfma32(kf[ks], qf[ks], s[0]);
+                kf[ks] = *(const half8 *)(kp + 32 * kPfKRow + ks * 16);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) s[1] = mfma32(kf[ks], qf[ks], s[1]);
+            if (n + 1 < ntiles) {
+                kr = load_tile(Kh, (long)(n + 1) * kPfN, L, tid);
+                vr = load_tile_vt(Vth, a.Lp, (long)(n + 1) * kPfN, tid);
             }
             float mx = m;
             if (key0 + kPfN - 1 > q0) {                // the diagonal crosses the tile: keys after the query are masked
@@ -248,6 +250,13 @@ __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
                         const half8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                         o[db] = mfma32(vf, pb[t][sx], o[db]);
                     }
+        } else if (n + 1 < ntiles) {                   // a wave that skips the tile still moves its share of the next one
+            kr = load_tile(Kh, (long)(n + 1) * kPfN, L, tid);
+            vr = load_tile_vt(Vth, a.Lp, (long)(n + 1) * kPfN, tid);
+        }
+        if (n + 1 < ntiles) {                          // the other buffer was last read before the previous barrier
+            store_tile_rowmajor(Ks + ((n + 1) & 1) * kPfKTile, kr, tid);
+            store_tile_vt(Vt + ((n + 1) & 1) * kPfVTile, vr, tid);
         }
         __syncthreads();                               // tile n+1 is in place, everyone is done with tile n
     }
