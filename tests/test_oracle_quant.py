@@ -137,3 +137,29 @@ def test_gather_takes_rows_in_ascending_order(ref):
     s = ref.RefShape(1, U, U, D, G, 128, 0); c = ref.RefCache(s)
     assert ref.quantize_pack(c, K, V, np.full((U,), 64, np.int32), bad) != 0
     assert ref.quantize_pack(c, K, V, np.full((U,), 40, np.int32), idx) != 0    # not a multiple of G
+
+
+@pytest.mark.parametrize("G", [16, 32])
+def test_keys_with_outlier_channels_quantize_better_per_channel_than_per_token(ref, G):
+    """Section 3.1.1 / the appendix on per-token key quantization: keys have a few large-magnitude CHANNELS, so
+    grouping a channel over tokens (the K path) keeps the outliers in groups of their own, while grouping a
+    token over channels (the V path, fed here with the same keys) lets one outlier set the step of its whole
+    group.  The same data through both paths of the oracle: the per-channel error is several times smaller."""
+    U, L, D = 2, 512, 128
+    K = _rand(U, L, D, 77 + G)
+    outliers = [3, 40, 41, 100]
+    K[:, :, outliers] *= 12
+    c = ref_cache_from(ref, K, K.copy(), G)               # V := K, so Vhat is K quantized per token
+    for u in range(U):
+        per_channel, per_token = ref.dequant(c, u)
+        x = K[u].astype(np.float64)
+        # the ordinary channels that share a channel group with an outlier pay for it under per-token grouping
+        groups = sorted({o // G for o in outliers})
+        victims = np.setdiff1d(np.concatenate([np.arange(gr * G, (gr + 1) * G) for gr in groups]), outliers)
+        e_ch = np.sqrt(np.mean((per_channel[:, victims] - x[:, victims]) ** 2))
+        e_tok = np.sqrt(np.mean((per_token[:, victims] - x[:, victims]) ** 2))
+        assert e_tok > 3 * e_ch, (e_ch, e_tok)
+        # channel groups without an outlier are unaffected: there the two groupings err alike
+        clean = np.arange(64, 96) if G == 32 else np.arange(64, 80)
+        r = np.sqrt(np.mean((per_token[:, clean] - x[:, clean]) ** 2)) / np.sqrt(np.mean((per_channel[:, clean] - x[:, clean]) ** 2))
+        assert 0.5 < r < 2.0
