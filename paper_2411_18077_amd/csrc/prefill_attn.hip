@@ -278,7 +278,7 @@ __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
     }
 }
 
-__global__ __launch_bounds__(256, 4) void prefill_colsum_kernel(PrefillArgs a)
+__global__ __launch_bounds__(256, 2) void prefill_colsum_kernel(PrefillArgs a)
 {
     __shared__ __align__(16) _Float16 Qs[2 * kPfKTile];
     __shared__ __align__(16) float lse2[2 * kPfN];     // LSE of the tile's queries, in powers of two (two buffers each)
