@@ -60,6 +60,17 @@ def test_peaked_and_flat_softmax_rows(g, gain, sm):
     check(g, 1, 4, 2, 500, seed=7, gain=gain, sm=sm)
 
 
+def test_random_shapes(g):
+    """Seeded sweep over batch, head counts, prompt lengths around the tile sizes (64 keys, 128 queries) and
+    softmax sharpness."""
+    rng = np.random.default_rng(7)
+    for case in range(16):
+        Hkv = int(rng.choice([1, 2, 3]))
+        rep = int(rng.choice([1, 2, 4, 5]))
+        L = int(rng.choice([rng.integers(1, 70), rng.integers(120, 136), rng.integers(190, 260), rng.integers(300, 900)]))
+        check(g, int(rng.integers(1, 3)), Hkv * rep, Hkv, L, seed=300 + case, gain=float(rng.choice([0.5, 1.0, 1.7])))
+
+
 def test_first_pass_alone(g):
     from oracle import ref
     Q, K, V = W.make_prefill_inputs(1, 2, 1, 200, 5, device="cuda")

@@ -81,13 +81,31 @@ def test_constant_and_monotone_scores(g):
     check(g, zeros, [7], [3])
 
 
-@pytest.mark.parametrize("rep,L", [(4, 1000), (2, 4099), (8, 333), (4, 40000)])
+@pytest.mark.parametrize("rep,L", [(4, 1000), (2, 4099), (8, 333), (4, 40000), (3, 5000), (5, 777), (16, 130)])
 def test_query_heads_of_a_group_are_summed(g, rep, L):
     U = 5
     A = W.make_scores(U * rep, L, seed=31 + rep, device="cuda", kind="attention")
     check(g, A, np.full(U, L // 4), np.full(U, L // 5), rep=rep)
     T = W.make_scores(U * rep, L, seed=32 + rep, device="cuda", kind="ties")
     check(g, T, np.full(U, L // 3), np.full(U, 0), rep=rep)
+
+
+def test_random_shapes_and_budgets(g):
+    """Seeded sweep: 40 random (units, heads per unit, prompt length, kind) with random budgets per unit, a
+    few of them out of range, and rows narrower than the prompt."""
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        U = int(rng.integers(1, 7))
+        rep = int(rng.choice([1, 1, 2, 3, 4, 6, 8]))
+        L = int(rng.choice([rng.integers(1, 200), rng.integers(200, 6000), rng.integers(30000, 36000)]))
+        kind = str(rng.choice(["attention", "ties", "signed"]))
+        A = W.make_scores(U * rep, L, seed=1000 + case, device="cuda", kind=kind)
+        n_rw = rng.integers(0, L + 1, U)
+        n_hh = np.array([rng.integers(0, L - w + 1) for w in n_rw])
+        if case % 5 == 0:
+            n_hh[0] = L + 1                                  # out of range: that unit keeps nothing
+        stride = int(rng.choice([L, max(1, L // 2), L + 3]))
+        check(g, A, n_hh.astype(np.int32), n_rw.astype(np.int32), rep=rep, idx_stride=stride)
 
 
 def test_empty_prompt_and_no_units(g):
