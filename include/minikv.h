@@ -146,7 +146,7 @@ int minikv_decode_attn(const minikv_shape *shape, const minikv_f16 *q, const min
  *   A_cumul    fp32 [B][Hq][L] or NULL (then only the first pass runs)   (device, written)
  *   workspace  device scratch of at least selective_flash_attn_workspace_bytes(B, Hkv, L) bytes, 16-byte
  *              aligned (a transposed copy of V: linear in L); contents private, no initial state required.
- * L >= 1, Hq % Hkv == 0, B*Hkv <= 65535, pointers 16-byte aligned, sm_scale finite and > 0. */
+ * 1 <= L <= 2^23 (a head's rows are addressed with 32-bit byte offsets), Hq % Hkv == 0, B*Hkv <= 65535, pointers 16-byte aligned, sm_scale finite and > 0. */
 size_t selective_flash_attn_workspace_bytes(int32_t B, int32_t Hkv, int64_t L);
 int selective_flash_attn(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, const minikv_f16 *Q, const minikv_f16 *K,
                          const minikv_f16 *V, float sm_scale, minikv_f16 *X_O, float *lse, float *A_cumul,

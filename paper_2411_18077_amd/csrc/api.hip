@@ -176,7 +176,7 @@ int selective_flash_attn(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, const mi
                          const minikv_f16 *V, float sm_scale, minikv_f16 *X_O, float *lse, float *A_cumul,
                          void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || L < 1 || L > ((int64_t)1 << 30)) return MINIKV_EINVAL;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || L < 1 || L > ((int64_t)1 << 23)) return MINIKV_EINVAL;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(X_O) || !aligned16(lse)) return MINIKV_EINVAL;
     if (A_cumul && ((uintptr_t)A_cumul & 15u)) return MINIKV_EINVAL;
     if (!aligned16(workspace)) return MINIKV_EINVAL;

@@ -57,20 +57,27 @@ __device__ __forceinline__ float16v mfma32(half8 a, half8 b, float16v c)
 // Row of accumulator element i (0..15) inside a 32x32 result tile, for a lane of half-wave g.
 __device__ __forceinline__ int acc_row(int i, int g) { return (i >> 2) * 8 + g * 4 + (i & 3); }
 
-// One tile of 64 rows x 128 halves from global memory: 4 chunks of 16 bytes per thread, coalesced.  Rows at or
-// beyond `rows_valid` are read from the last valid row (their products are masked or discarded later).
+// Tiles come from global memory through buffer loads: a descriptor (base, byte size) per head in scalar
+// registers, ONE loop-invariant byte offset per lane and a scalar offset per tile and chunk, so the loop spends
+// no vector instructions on addresses; bytes beyond the size read as zero (rows past the end of the prompt).
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+constexpr int kRawBufferFlags = 0x00020000;   // raw buffer, 32-bit data format
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_of(const void *base, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, kRawBufferFlags);
+}
 struct TileRegs {
     uint4 c[4];
 };
-__device__ __forceinline__ TileRegs load_tile(const _Float16 *base, long row0, long rows_valid, int tid)
+// One tile of 64 rows x 128 halves (rows are 256 bytes, so chunk k of the tile is at byte 16 k): 4 chunks of 16
+// bytes per thread, coalesced.  lane_off = 16 * tid.
+__device__ __forceinline__ TileRegs load_tile(__amdgpu_buffer_rsrc_t rs, unsigned lane_off, unsigned tile_off)
 {
     TileRegs t;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int chunk = tid + 256 * i;                 // row = chunk / 16, 8 halves at (chunk % 16) * 8
-        long row = row0 + (chunk >> 4);
-        row = row < rows_valid ? row : rows_valid - 1;
-        t.c[i] = *(const uint4 *)(base + row * kPfD + (chunk & 15) * 8);
+        const uint4v v = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, tile_off + 4096u * i, 0);
+        t.c[i] = make_uint4(v[0], v[1], v[2], v[3]);
     }
     return t;
 }
@@ -82,14 +89,16 @@ __device__ __forceinline__ void store_tile_rowmajor(_Float16 *lds, const TileReg
         *(uint4 *)(lds + (chunk >> 4) * kPfKRow + (chunk & 15) * 8) = t.c[i];
     }
 }
-// One tile of 128 channels x 64 keys of the transposed V: chunk = 8 keys of one channel.
-__device__ __forceinline__ TileRegs load_tile_vt(const _Float16 *vt, long Lp, long key0, int tid)
+// One tile of 128 channels x 64 keys of the transposed V: chunk = 8 keys of one channel, channel = chunk / 8.
+// lane_off = (tid / 8) * row_bytes + (tid % 8) * 16; chunk tid + 256 i is 32 i rows further down.
+__device__ __forceinline__ TileRegs load_tile_vt(__amdgpu_buffer_rsrc_t rs, unsigned lane_off, unsigned key_off,
+                                                 unsigned row_bytes)
 {
     TileRegs t;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int chunk = tid + 256 * i;                 // channel = chunk / 8, 8 keys at (chunk % 8) * 8
-        t.c[i] = *(const uint4 *)(vt + (long)(chunk >> 3) * Lp + key0 + (chunk & 7) * 8);
+        const uint4v v = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, key_off + 32u * i * row_bytes, 0);
+        t.c[i] = make_uint4(v[0], v[1], v[2], v[3]);
     }
     return t;
 }
@@ -166,7 +175,10 @@ __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
     // Two LDS buffers, one barrier per tile.  The global loads of tile n+1 are issued after the score products
     // of tile n (whose K fragments can then use those registers) and stored to the other buffer at the end of
     // the iteration, behind the softmax and the output products.
-    TileRegs kr = load_tile(Kh, 0, L, tid), vr = load_tile_vt(Vth, a.Lp, 0, tid);
+    const __amdgpu_buffer_rsrc_t krs = buffer_of(Kh, (unsigned)(L * kPfD * 2)), vrs = buffer_of(Vth, (unsigned)(kPfD * a.Lp * 2));
+    const unsigned row_bytes = (unsigned)(a.Lp * 2), k_lane = tid * 16u, v_lane = (tid >> 3) * row_bytes + (tid & 7) * 16u;
+    constexpr unsigned kKTileBytes = kPfN * kPfD * 2, kVTileBytes = kPfN * 2;
+    TileRegs kr = load_tile(krs, k_lane, 0), vr = load_tile_vt(vrs, v_lane, 0, row_bytes);
     store_tile_rowmajor(Ks, kr, tid);
     store_tile_vt(Vt, vr, tid);
     // Every load so far (the Q rows among them) has returned by now, since loads return in order and the stores
@@ -198,8 +210,8 @@ __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) s[1] = mfma32(kf[ks], qf[ks], s[1]);
             if (n + 1 < ntiles) {
-                kr = load_tile(Kh, (long)(n + 1) * kPfN, L, tid);
-                vr = load_tile_vt(Vth, a.Lp, (long)(n + 1) * kPfN, tid);
+                kr = load_tile(krs, k_lane, (n + 1) * kKTileBytes);
+                vr = load_tile_vt(vrs, v_lane, (n + 1) * kVTileBytes, row_bytes);
             }
             float mx = m;
             if (key0 + kPfN - 1 > q0) {                // the diagonal crosses the tile: keys after the query are masked
@@ -251,8 +263,8 @@ __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
                         o[db] = mfma32(vf, pb[t][sx], o[db]);
                     }
         } else if (n + 1 < ntiles) {                   // a wave that skips the tile still moves its share of the next one
-            kr = load_tile(Kh, (long)(n + 1) * kPfN, L, tid);
-            vr = load_tile_vt(Vth, a.Lp, (long)(n + 1) * kPfN, tid);
+            kr = load_tile(krs, k_lane, (n + 1) * kKTileBytes);
+            vr = load_tile_vt(vrs, v_lane, (n + 1) * kVTileBytes, row_bytes);
         }
         if (n + 1 < ntiles) {                          // the other buffer was last read before the previous barrier
             store_tile_rowmajor(Ks + ((n + 1) & 1) * kPfKTile, kr, tid);
@@ -303,14 +315,17 @@ __global__ __launch_bounds__(256, 2) void prefill_colsum_kernel(PrefillArgs a)
     float colsum = 0.0f;
     const float c = a.scale_log2;
     const int tile0 = (int)(((long)kb * kPfM) / kPfN), ntiles = (int)((L + kPfN - 1) / kPfN);
-    TileRegs qr = load_tile(Qh, (long)tile0 * kPfN, L, tid);
+    const __amdgpu_buffer_rsrc_t qrs = buffer_of(Qh, (unsigned)(L * kPfD * 2));
+    const unsigned q_lane = tid * 16u;
+    constexpr unsigned kQTileBytes = kPfN * kPfD * 2;
+    TileRegs qr = load_tile(qrs, q_lane, tile0 * kQTileBytes);
     float lr = 0.0f;
     if (tid < kPfN) lr = lseh[min((long)tile0 * kPfN + tid, L - 1)];
     store_tile_rowmajor(Qs, qr, tid);
     if (tid < kPfN) lse2[tid] = lr * kLog2e;
     __builtin_amdgcn_s_waitcnt(kWaitVm0);              // as in the first pass: the K rows have arrived
     if (tile0 + 1 < ntiles) {
-        qr = load_tile(Qh, (long)(tile0 + 1) * kPfN, L, tid);
+        qr = load_tile(qrs, q_lane, (tile0 + 1) * kQTileBytes);
         if (tid < kPfN) lr = lseh[min((long)(tile0 + 1) * kPfN + tid, L - 1)];
     }
     __syncthreads();
@@ -323,7 +338,7 @@ __global__ __launch_bounds__(256, 2) void prefill_colsum_kernel(PrefillArgs a)
             if (tid < kPfN) lse2[(cur ^ 1) * kPfN + tid] = lr * kLog2e;
         }
         if (n + 2 < ntiles) {
-            qr = load_tile(Qh, (long)(n + 2) * kPfN, L, tid);
+            qr = load_tile(qrs, q_lane, (n + 2) * kQTileBytes);
             if (tid < kPfN) lr = lseh[min((long)(n + 2) * kPfN + tid, L - 1)];
         }
         const long qt0 = (long)n * kPfN;
