@@ -19,6 +19,8 @@
 //                          adds the weights of its key column in the lane: no atomics, one exchange at the end.
 #include "common.h"
 
+#include <type_traits>
+
 namespace minikv {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -345,31 +347,38 @@ __global__ __launch_bounds__(256, 2) void prefill_colsum_kernel(PrefillArgs a)
         if (qt0 + kPfN - 1 >= k0) {                    // else every query of the tile precedes every key of this wave
             const bool edge = qt0 < k0 + 31 || qt0 + kPfN > L;   // the diagonal or the end of the prompt crosses the tile
             const int lo_q = (int)(key - qt0), hi_q = (int)min(L - qt0, (long)kPfN);   // tile rows lo_q .. hi_q-1 count
+            // two copies of the tile's work, chosen per tile: only the few edge tiles pay for the masking
+            auto tile = [&](auto masked) {
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                float16v s;
+                for (int t = 0; t < 2; ++t) {
+                    float16v s;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) s[i] = 0.0f;
+                    for (int i = 0; i < 16; ++i) s[i] = 0.0f;
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    const half8 qf = *(const half8 *)(Qc + (t * 32 + r) * kPfKRow + ks * 16 + g * 8);
-                    s = mfma32(qf, kf[ks], s);
-                }
+                    for (int ks = 0; ks < 8; ++ks) {
+                        const half8 qf = *(const half8 *)(Qc + (t * 32 + r) * kPfKRow + ks * 16 + g * 8);
+                        s = mfma32(qf, kf[ks], s);
+                    }
 #pragma unroll
-                for (int iq = 0; iq < 4; ++iq) {
-                    const float4 ls = *(const float4 *)&lc[t * 32 + iq * 8 + g * 4];
-                    const float lsv[4] = {ls.x, ls.y, ls.z, ls.w};
+                    for (int iq = 0; iq < 4; ++iq) {
+                        const float4 ls = *(const float4 *)&lc[t * 32 + iq * 8 + g * 4];
+                        const float lsv[4] = {ls.x, ls.y, ls.z, ls.w};
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[iq * 4 + j], c, -lsv[j]));
-                        if (edge) {
-                            const int row = t * 32 + iq * 8 + g * 4 + j;
-                            if (row < lo_q || row >= hi_q) p = 0.0f;
+                        for (int j = 0; j < 4; ++j) {
+                            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[iq * 4 + j], c, -lsv[j]));
+                            if (decltype(masked)::value) {
+                                const int row = t * 32 + iq * 8 + g * 4 + j;
+                                if (row < lo_q || row >= hi_q) p = 0.0f;
+                            }
+                            colsum += p;
                         }
-                        colsum += p;
                     }
                 }
-            }
+            };
+            if (edge)
+                tile(std::true_type{});
+            else
+                tile(std::false_type{});
         }
         __syncthreads();
     }
