@@ -61,6 +61,18 @@ def test_prompts_longer_than_the_on_chip_key_cache(g, L):
         check(g, A, [L // 4, 1, L - 100], [L // 4, L // 2, 100])
 
 
+@pytest.mark.parametrize("L", [40000, 200000])
+def test_scores_tied_en_masse(g, L):
+    """More equal or near-equal scores than the on-chip candidate list holds (16384): constant scores, eight
+    levels, and attention-like scores squeezed into one binade take the general path of the kernel."""
+    flat = torch.full((2, L), 3.5, device="cuda")
+    check(g, flat, [L // 3, 17], [L // 4, 0], idx_stride=L)
+    ties = W.make_scores(2, L, seed=L, device="cuda", kind="ties")
+    check(g, ties, [L // 3, L // 2], [L // 4, 5], idx_stride=L)
+    narrow = (1.0 + W.make_scores(4, L, seed=L + 1, device="cuda", kind="attention").clamp_(max=1.0) * 2.0 ** -12).contiguous()
+    check(g, narrow, np.full(2, L // 5), np.full(2, L // 5), rep=2, idx_stride=L)
+
+
 def test_ragged_degenerate_and_invalid_budgets(g):
     L = 777
     A = W.make_scores(12, L, seed=6, device="cuda", kind="ties")
