@@ -6,7 +6,11 @@
  * fp16 scale and zero-point and 16 codes per 32-bit word (Section 3.1.1, Section 3.3), the fp16
  * residual buffer that is compressed every n_r steps (Section 3.3, Algorithm 1 lines 9-15) and the
  * decode attention with dequantization fused into both products (Algorithm 1 lines 17-19), whose
- * result is softmax(q K^T * sm_scale) V of Appendix A eq. (1) over the compressed cache.
+ * result is softmax(q K^T * sm_scale) V of Appendix A eq. (1) over the compressed cache.  Two prefill-side
+ * calls produce what those consume: the causal prompt attention that also returns every token's cumulative
+ * attention score in linear memory (Section 3.2, Algorithm 1 line 2) and the heavy-hitter + recent-window
+ * selection of the kept positions (Section 3.1.2, Algorithm 1 line 3), with the pyramid layer budget
+ * (Section 3.1.3) as host arithmetic.
  *
  * Conventions
  *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned; the library never
