@@ -116,6 +116,39 @@ def test_long_prompt_on_sampled_rows_and_columns(g):
     assert np.all(np.abs(got - col) <= RTOL_A * np.abs(col) + ATOL_A)
 
 
+def test_million_token_prompt_addressing(g):
+    """One head, 2^20 + 77 tokens: the tile offsets are 32-bit byte offsets per head (268 MB of K, 2 MB rows of
+    the transposed V), so this checks them at scale.  Compared in float64 with numpy: X_O and LSE of sampled
+    query rows over the whole prompt, A_cumul of the last 150 columns (they only need the last 150 rows), and
+    the exact property sum_j A_cumul[j] = L."""
+    L = (1 << 20) + 77
+    sm = 1.0 / math.sqrt(128)
+    Q, K, V = W.make_prefill_inputs(1, 1, 1, L, 31, device="cuda")
+    xo, lse, acc = run_gpu(Q, K, V, sm)
+    got_a = g.to_np(acc[0, 0]).astype(np.float64)
+    assert np.isfinite(got_a).all() and abs(got_a.sum() - L) <= 1e-4 * L
+    k = g.to_np(K[0, 0]).astype(np.float64)
+    v = g.to_np(V[0, 0]).astype(np.float64)
+    scale = np.float64(np.float32(sm))
+
+    def rows_ref(rows):
+        S = (g.to_np(Q[0, 0][rows]).astype(np.float64) @ k.T) * scale
+        S[np.arange(L)[None, :] > rows[:, None]] = -np.inf
+        m = S.max(-1, keepdims=True)
+        E = np.exp(S - m)
+        den = E.sum(-1, keepdims=True)
+        return E / den, (m + np.log(den))[:, 0]
+
+    rows = np.array([0, 63, 64, 4095, 65536, 65537, 524288, 1000003, L - 129, L - 2, L - 1])
+    P, lse_ref = rows_ref(rows)
+    assert np.max(np.abs(g.to_np(xo[0, 0][rows]).astype(np.float64) - P @ v)) <= TOL_O
+    assert np.max(np.abs(g.to_np(lse[0, 0][rows]).astype(np.float64) - lse_ref)) <= TOL_LSE
+    tail = np.arange(L - 150, L)
+    P, _ = rows_ref(tail)
+    col = P[:, L - 150:].sum(0)
+    assert np.all(np.abs(got_a[L - 150:] - col) <= RTOL_A * np.abs(col) + ATOL_A)
+
+
 def test_prefill_select_quantize_decode_chain(g):
     """Algorithm 1 lines 2-5, then a decode step (lines 9, 17-19), all on the GPU; each stage is checked
     against the oracle fed with the GPU's input to that stage (the selection decides on the GPU's fp32
