@@ -73,6 +73,12 @@ def test_scores_tied_en_masse(g, L):
     check(g, narrow, np.full(2, L // 5), np.full(2, L // 5), rep=2, idx_stride=L)
 
 
+def test_million_token_prompt(g):
+    L = (1 << 20) + 5
+    A = W.make_scores(4, L, seed=3, device="cuda", kind="attention")
+    check(g, A, [L // 4, 1000], [L // 8, L // 2], rep=2, idx_stride=L // 2 + 1000)
+
+
 def test_ragged_degenerate_and_invalid_budgets(g):
     L = 777
     A = W.make_scores(12, L, seed=6, device="cuda", kind="ties")
