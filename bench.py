@@ -333,6 +333,13 @@ def main():
                     "flops = 6*D per causal (query, key) pair; peak 2500 TFLOP/s (dense fp16 matrix instructions)",
             "this_shape": time_prefill(1, w.Hq, w.Hkv, w.L, 3),
             "paper_table_longest": time_prefill(1, 32, 32, 8192, 10),
+            "paper_table_lengths": {
+                "what": "ms at the four lengths of the paper's kernel latency table (32 heads of 128, one sequence; "
+                        "the table's own batch and head count are not stated), next to its A100-40GB figures",
+                "L": [1024, 2048, 4096, 8192],
+                "ms": [time_prefill(1, 32, 32, Lt, 10)["ms"] for Lt in (1024, 2048, 4096, 8192)],
+                "paper_ms_a100": [5.21, 14.85, 48.04, 187.83],
+            },
         }
         result["build_s"] = round(t_build, 1)
 
