@@ -17,7 +17,11 @@
  *     allocates, frees or synchronises.  All work is enqueued on `stream` (a hipStream_t passed as
  *     void*; NULL = the default stream).  Lengths live in device memory so a decode loop never waits
  *     for the host.
- *   - fp16 = IEEE binary16 bit patterns (minikv_f16).  Inputs must be finite.
+ *   - fp16 = IEEE binary16 bit patterns (minikv_f16).  Inputs must be finite (no infinity, no NaN); every
+ *     finite value is accepted.  minikv_decode_attn forms its matrix operands in fp16 and is fastest while
+ *     |q_c * Ks| < 65504 for every channel and every V scale is below 4096 (a V group range below 12288);
+ *     a (batch, KV head) unit that leaves this range is detected on the device and recomputed with
+ *     range-normalised operands: same result to the stated tolerance, up to twice the time for that unit.
  *   - A "unit" is one (batch, KV head): u = b * Hkv + h.  Query head hq reads unit b*Hkv + hq/(Hq/Hkv).
  *   - Return value: MINIKV_OK (0) or a negative minikv_status; all checks happen on the host before
  *     anything is launched.  Values held in device memory (lengths, indices) are not validated; the
@@ -93,8 +97,13 @@ typedef enum {
 int         minikv_abi_version(void);
 const char *minikv_strerror(int status);
 
-/* Host-only helpers.  Bytes the caller must allocate for buffer `which` of a cache of this shape
- * (0 on an invalid shape), and for the split-K workspace of minikv_decode_attn. */
+/* Host-only helpers.  Bytes the caller must allocate for buffer `which` (a minikv_buffer) of a cache of
+ * this shape, 0 on an invalid shape: per retained token 64 + 8*D/G bytes over the six packed buffers
+ * (16 codes per 32-bit word plus an fp16 scale and zero-point per group, the storage arithmetic of the
+ * paper's appendix on KV cache sizes), 4*D bytes per residual token, 4 bytes per length.
+ * minikv_buffer_bytes is the same function under its earlier name.  minikv_workspace_bytes: bytes of the
+ * split-K workspace of minikv_decode_attn. */
+size_t minikv_cache_bytes(const minikv_shape *shape, int which);
 size_t minikv_buffer_bytes(const minikv_shape *shape, int which);
 size_t minikv_workspace_bytes(const minikv_shape *shape);
 
@@ -106,8 +115,8 @@ size_t minikv_workspace_bytes(const minikv_shape *shape);
  *   idx      int32 [B*Hkv][idx_stride] or NULL              (device, read)
  *   n_tok    int32 [B*Hkv], each a multiple of G, <= L      (device, read)
  *   max_tok  host-side upper bound of every n_tok[u] (sizes the launch; multiple of G, <= Tcap)
- * A unit whose q_len[u] + n_tok[u] would exceed Tcap, or whose n_tok is not a positive multiple of G,
- * is left unchanged. */
+ * A unit whose q_len[u] + n_tok[u] would exceed Tcap, whose n_tok is not a positive multiple of G, or whose
+ * n_tok exceeds max_tok is left unchanged. */
 int kv_quantize_pack(const minikv_shape *shape, const minikv_f16 *K, const minikv_f16 *V, int64_t L,
                      const int32_t *idx, int64_t idx_stride, const int32_t *n_tok, int32_t max_tok,
                      minikv_cache *cache, void *stream);
@@ -186,17 +195,6 @@ int kv_select_hh_rw(int32_t units, int32_t rep, int64_t L, const float *A_cumul,
  *   budget  double [n_layers]                                             (HOST, written)
  * Returns MINIKV_EINVAL for n_layers < 1, d < 1, x < 0 or NaN, or a null pointer. */
 int kv_pyramid_budget(int32_t n_layers, double x, int32_t d, int32_t bottom_heavy, double *budget);
-
-/* Diagnostics: a plain streaming read (128-bit loads, 2048 workgroups) of `bytes` bytes (rounded down to 16) at
- * src, the reference point the bandwidth figures are compared with.  sums: uint32 [2048] (device), xor-updated
- * with a checksum per workgroup. */
-int minikv_stream_read_probe(const void *src, size_t bytes, uint32_t *sums, void *stream);
-
-/* Diagnostics: selects the kernel variant minikv_decode_attn launches (process-wide).
- *   0 = default (fastest verified), 1 = plain scalar-loop kernel kept for cross-checks,
- *   others as listed by minikv_strvariant().  Returns MINIKV_EINVAL for an unknown id. */
-int         minikv_set_variant(int variant);
-const char *minikv_strvariant(int variant);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,30 @@
+/*
+ * libminikv diagnostics -- entry points that serve measurements and cross-checks, not the decode path.
+ * They are exported by the same shared library and follow the conventions of minikv.h (device pointers
+ * owned by the caller, work enqueued on `stream`, negative minikv_status on a host-side check).
+ */
+#ifndef MINIKV_DIAG_H
+#define MINIKV_DIAG_H
+
+#include "minikv.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* A plain streaming read (128-bit loads, 2048 workgroups) of `bytes` bytes (rounded down to 16) at src: the
+ * reference point the bandwidth figures of the decode kernel are compared with.  sums: uint32 [2048] (device),
+ * xor-updated with a checksum per workgroup. */
+int minikv_stream_read_probe(const void *src, size_t bytes, uint32_t *sums, void *stream);
+
+/* Selects the kernel minikv_decode_attn launches (process-wide):
+ *   0 = default, 1 = a plain scalar-loop fp32 kernel (two launches) kept as a second GPU implementation of
+ *   Algorithm 1 lines 17-19 for cross-checks, 3 = the default kernel by its own number.
+ * Returns MINIKV_EINVAL for any other id.  minikv_strvariant names an id. */
+int         minikv_set_variant(int variant);
+const char *minikv_strvariant(int variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

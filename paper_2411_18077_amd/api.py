@@ -52,6 +52,8 @@ def lib():
         l.minikv_set_variant.argtypes = [C.c_int]
         l.minikv_buffer_bytes.restype = C.c_size_t
         l.minikv_buffer_bytes.argtypes = [C.POINTER(MinikvShape), C.c_int]
+        l.minikv_cache_bytes.restype = C.c_size_t
+        l.minikv_cache_bytes.argtypes = [C.POINTER(MinikvShape), C.c_int]
         l.minikv_workspace_bytes.restype = C.c_size_t
         l.minikv_workspace_bytes.argtypes = [C.POINTER(MinikvShape)]
         P = C.c_void_p
@@ -105,18 +107,22 @@ def buffer_bytes(shape, which):
     return int(lib().minikv_buffer_bytes(C.byref(shape), which))
 
 
+def cache_bytes(shape, which):
+    return int(lib().minikv_cache_bytes(C.byref(shape), which))
+
+
 def workspace_bytes(shape):
     return int(lib().minikv_workspace_bytes(C.byref(shape)))
 
 
 class Cache:
-    """Caller-owned device buffers of one cache (torch tensors), sized by minikv_buffer_bytes."""
+    """Caller-owned device buffers of one cache (torch tensors), sized by minikv_cache_bytes."""
 
     def __init__(self, shape, device="cuda", fill=None):
         self.shape = shape
         self.t = {}
         for i, name in enumerate(BUF_NAMES):
-            nbytes = buffer_bytes(shape, i)
+            nbytes = cache_bytes(shape, i)
             dt = _BUF_DTYPE[name]
             n = max(nbytes // dt.itemsize, 1)         # Rcap == 0: a 1-element placeholder
             self.t[name] = torch.zeros(n, dtype=dt, device=device)

@@ -1,5 +1,6 @@
 // Host side of libminikv: argument checks, buffer sizes, launch geometry, C entry points.
 #include "common.h"
+#include "minikv_diag.h"
 
 #include <atomic>
 
@@ -86,6 +87,8 @@ const char *minikv_strerror(int status)
     default: return "unknown status";
     }
 }
+
+size_t minikv_cache_bytes(const minikv_shape *s, int which) { return minikv_buffer_bytes(s, which); }
 
 size_t minikv_buffer_bytes(const minikv_shape *s, int which)
 {
@@ -210,10 +213,13 @@ int kv_select_hh_rw(int32_t units, int32_t rep, int64_t L, const float *A_cumul,
 int kv_pyramid_budget(int32_t n_layers, double x, int32_t d, int32_t bottom_heavy, double *budget)
 {
     if (n_layers < 1 || d < 1 || !(x >= 0.0) || !budget) return MINIKV_EINVAL;
-    const double small_end = x / d, large_end = 2.0 * x - x / d;
-    const double first = bottom_heavy ? large_end : small_end, last = bottom_heavy ? small_end : large_end;
-    for (int32_t l = 0; l < n_layers; ++l)
-        budget[l] = n_layers == 1 ? x : first + (last - first) * l / (n_layers - 1);
+    // The budgets are symmetric about x: layer l holds x + t * (x - x/d) with t running from -1 at one end
+    // layer to +1 at the other, so the ends are x/d and 2x - x/d and the mean is x.
+    const double half_range = x - x / (double)d;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const double t = n_layers == 1 ? 0.0 : (2.0 * l - (n_layers - 1)) / (double)(n_layers - 1);
+        budget[l] = x + (bottom_heavy ? -t : t) * half_range;
+    }
     return MINIKV_OK;
 }
 
@@ -227,7 +233,7 @@ int minikv_stream_read_probe(const void *src, size_t bytes, uint32_t *sums, void
 
 int minikv_set_variant(int variant)
 {
-    if (variant < 0 || variant > 4 || variant == 2) return MINIKV_EINVAL;
+    if (!(variant == 0 || variant == 1 || variant == 3)) return MINIKV_EINVAL;
     g_variant.store(variant);
     return MINIKV_OK;
 }
@@ -238,7 +244,6 @@ const char *minikv_strvariant(int variant)
     case 0: return "default";
     case 1: return "scalar: plain per-token loops, fp32 FMA (cross-check kernel)";
     case 3: return "wave-tiled, 4x4x4 fp16 matrix-core blocks for the head x channel products";
-    case 4: return "as 3 but the q*Ks table keeps only its rounded fp16 value (no exact hi+lo pair)";
     default: return "unknown";
     }
 }

@@ -32,7 +32,9 @@
 //     like the K words and multiplied 4 tokens x 4 heads at a time.  The zero-point term is accumulated
 //     per lane in fp32 and reduced once per unit and wave.
 //
-// Input domain implied by the fp16 operands: |q * Ks| < 65504 and Vs < 4096 (V group range < 12288).
+// Input domain: every finite fp16 input.  The fp16 operands of the matrix instructions hold |q * Ks| < 65504
+// and V scales < 4096 with the default scalings; a wave whose sums show an overflow repeats its share of the
+// unit with range-normalised operands (see "Operand ranges" in the kernel).
 #include "decode_wave.h"
 
 namespace minikv {
@@ -90,23 +92,6 @@ __device__ inline float *slot_ptr(const DecArgs &a, int slot, int h)
     return a.ws + ((size_t)slot * kNH + h) * kPartialStride;
 }
 
-// Optional per-wave cycle accounting for tuning (compiled in only with -DMINIKV_TIMELINE).
-#ifdef MINIKV_TIMELINE
-__device__ long long g_qtl[16384 * 24];
-#define QT_NOW() __builtin_readcyclecounter()
-#define QT_SET(slot, v) do { qt[slot] = (long long)(v); } while (0)
-#define QT_ADD(slot, v) do { qt[slot] += (long long)(v); } while (0)
-#define QT_MARK(var) const long long var = QT_NOW()
-extern "C" int minikv_debug_qtl(long long *host, int n)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_qtl), (size_t)n * 8, 0, hipMemcpyDeviceToHost);
-}
-#else
-#define QT_SET(slot, v) do {} while (0)
-#define QT_ADD(slot, v) do {} while (0)
-#define QT_MARK(var) do {} while (0)
-#endif
-
 // Two waves per SIMD, except for G = 16, whose per-lane share of the K scale / zero rows and of q*Ks does not
 // fit 256 registers: one wave per SIMD with the full register file runs 1.6x faster there than two that
 // spill (the pass loop is bound by instruction issue, which one wave nearly saturates).
@@ -135,13 +120,6 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
 
     const int lane = threadIdx.x;
     const int NU = a.units * a.hsets;
-#ifdef MINIKV_TIMELINE
-    long long qt[24];                                      // kept in registers, written once at the end
-    for (int i = 0; i < 24; i++) qt[i] = 0;
-    QT_SET(0, __builtin_amdgcn_s_memrealtime());
-    { unsigned hwid, xcc; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid)); asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc)); QT_SET(13, (long long)hwid | ((long long)xcc << 32)); }
-#endif
-    QT_MARK(t_begin);
 
     // ---------------- the work list: total weight P, this wave's range, the unit that holds its start.
     // Lane l looks at units l, l+64, ...; up to 256 units the lengths stay in registers between the two
@@ -193,8 +171,6 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             if (it.nq + it.nr == 0) zero_fill(uu);
         }
     }
-    QT_MARK(t_sum);
-    QT_ADD(22, t_sum - t_begin);
     // The weight line is cut into NW ranges, each at least one residual item long.  NW is a power of two so
     // that the cuts need no division.
     if (P == 0) return;
@@ -244,8 +220,6 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
         }
     }
     const int up_first = up;
-    QT_MARK(t_prol);
-    QT_ADD(2, t_prol - t_begin);
 
     const int blk4 = lane >> 2, row = lane & 3;            // block of 4 lanes; row = query head this lane
                                                            // supplies as A operand
@@ -257,14 +231,10 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
     // Tokens 2*lane, 2*lane+1 are field j = lane & 7 of their V word.  The weights of this lane carry the
     // constant factor 2^lg = 16 * 4^-shift so that the masked V field needs no shift; the lane's running
     // sums l and oz carry the same factor and are unscaled once per unit.
-    const float lg = 4.0f - (float)fld_shift(lane & 7);
-    const float unlg = fast_exp2(-lg);
     const float kscale = a.c1 * 16777216.0f;               // undo the 2^-24 of the subnormal code fields
-    const float vun = 16777216.0f / 16.0f;                 // 2^24 (subnormal fields) / 2^4 (ps headroom)
 
     // A wave owns the items whose start position lies in [start, end).
     for (; up < NU && ib < end; up++) {
-        QT_MARK(t_u0);
         // (the lengths of the first unit are already known)
         const UnitItems it = up == up_first ? UnitItems{(T_first + kPass - 1) / kPass, (R_first + 63) / 64, T_first, R_first}
                                             : unit_items(a, up);
@@ -293,13 +263,16 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
         const uint16_t *Vs = a.Vs + (size_t)u * a.Tcap * NCG;
         const uint16_t *Vz = a.Vz + (size_t)u * a.Tcap * NCG;
 
+        int lane_u = lane;
+        asm volatile("" : "+v"(lane_u));                   // (opaque copy: per-lane load offsets are set up per unit)
+        const int bbk_u = (lane_u >> 2) % BGK;
         auto load_k = [&](int tp) -> KD {
             KD d;
             const u4 *ktile = reinterpret_cast<const u4 *>(Kc + (size_t)(tp >> 7) * 1024);
 #pragma unroll
             for (int i = 0; i < 4; i++) d.kw[i] = ktile[i * 64 + lane];
             const bool gvalid = tp + gl * G < t_end;
-            const size_t go = ((size_t)(tp / G) + (gvalid ? gl : 0)) * kD + bbk * (NKR * 4);
+            const size_t go = ((size_t)(tp / G) + (gvalid ? gl : 0)) * kD + bbk_u * (NKR * 4);
             d.ks = load_words<NKW>(Ks + go);
             d.kz = load_words<NKW>(Kz + go);
             return d;
@@ -321,6 +294,25 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             return d;
         };
 
+        // Operand ranges.  The A operands of both products are fp16: q*Ks*4^-j on the K side and p*Vs*2^lg on
+        // the V side (p <= 1, 2^lg <= 2^hd).  The first attempt uses the scalings that keep the most precision
+        // (q as it is, hd = 4); they hold as long as |q*Ks| < 65504 and Vs < 4096.  Beyond that an operand
+        // overflows to infinity, which ends up in the wave's sums: an infinite q*Ks meets a code 0 in its group
+        // (every group with a non-zero scale has one), the product is NaN, so is that token's weight, and the sum
+        // of weights keeps it; an infinite p*Vs makes the output sums infinite or NaN.  The sums are checked once
+        // per unit, and if one is not finite the wave does its items of the unit again with q scaled per head to
+        // below 1 and hd = -1: then |A| <= max Ks, max Vs / 2 <= 43669 whatever the inputs (the largest fp16
+        // scale is (65504 + 65504) / 3).  No cost for data inside the range; outside it the result keeps fewer
+        // bits of the small weights.
+        float m[kNH], lsum[kNH];                           // running max; sum of weights (wave-uniform at the end)
+        float oa[kNH], ob[kNH];                            // un-normalised output of channels lane, lane+64
+#pragma nounroll
+        for (int attempt = 0; attempt < 2; attempt++) {
+        const bool safe = attempt != 0;
+        const float hd = safe ? -1.0f : 4.0f;
+        const float lg = hd - (float)fld_shift(lane & 7);
+        const float vun = safe ? 33554432.0f : 1048576.0f; // 2^24 (subnormal fields) / 2^hd (ps headroom)
+        const float inv_vun = 1.0f / vun;
         // The tiles of the first pass are requested before anything else is waited for.
         KD kd = {};
         VD vd = {};
@@ -329,7 +321,7 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             vd = load_v(j0 * kPass);
         }
         // the wave's online-softmax state for this unit
-        float m[kNH], l_lane[kNH];
+        float l_lane[kNH];
         f4 O0 = {0.f, 0.f, 0.f, 0.f}, O1 = {0.f, 0.f, 0.f, 0.f};   // channel lane / lane+64, 4 heads each
         float oz[kNH][NCG];
 #pragma unroll
@@ -338,8 +330,6 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
 #pragma unroll
             for (int g = 0; g < NCG; g++) oz[h][g] = 0.f;
         }
-        QT_MARK(t_u1);
-        QT_ADD(3, t_u1 - t_u0);
 
         // =============================== residual items (64 fp16 tokens each): Algorithm 1's R_K t_Q^T and
         // A_unquant R_V, on the same 4x4x4 matrix instruction as the quantized passes (the vector ALU is
@@ -349,8 +339,6 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
         // read back as the B operand, q as the A operand broadcast to all 16 blocks.  Values: lane =
         // channels lane, lane+64, the B operand gathered token by token from the staged rows, the weights
         // p (fp16, through LDS) as the broadcast A operand.  The result is folded into the wave's state.
-        float lsum[kNH];                                   // sum of weights (wave-uniform after the reduction)
-        float oa[kNH], ob[kNH];                            // un-normalised output of channels lane, lane+64
         auto residual_items = [&](int lo, int hi, int odd) {   // even items sit before the passes, odd ones after
 #pragma unroll 1
         for (int fi = lo; fi < hi; fi++) {
@@ -361,11 +349,12 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             constexpr int kPrH = 72;
             const uint16_t *Rk = a.Rk + (size_t)u * a.Rcap * kD;
             const uint16_t *Rv = a.Rv + (size_t)u * a.Rcap * kD;
-            const int rsub = lane >> 4, piece = lane & 15;  // row within a group of 4, 16-byte piece of the row
+            int lane_r = lane;                             // (opaque copy: keeps the address terms below out of
+            asm volatile("" : "+v"(lane_r));               //  the registers that live across the pass loop)
+            const int rsub = lane_r >> 4, piece = lane_r & 15;  // row within a group of 4, 16-byte piece of the row
             const int t0 = ri * 64;
             const bool valid = t0 + lane < R;
 
-            QT_MARK(t_r0);
             Words<64> g;
 #pragma unroll
             for (int i = 0; i < 16; i++) {
@@ -394,8 +383,6 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                 g.v[4 * i] = x.x; g.v[4 * i + 1] = x.y; g.v[4 * i + 2] = x.z; g.v[4 * i + 3] = x.w;
             }
             __builtin_amdgcn_wave_barrier();
-            QT_MARK(t_r1);
-            QT_ADD(16, t_r1 - t_r0);
 
             f4 sc = {0.f, 0.f, 0.f, 0.f};                  // scores of token t0 + lane for the 4 heads
 #pragma unroll
@@ -411,8 +398,6 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                 *reinterpret_cast<uint4 *>(rows + (4 * i + rsub) * kKRowH + piece * 8) =
                     uint4{g.v[4 * i], g.v[4 * i + 1], g.v[4 * i + 2], g.v[4 * i + 3]};
 
-            QT_MARK(t_r2);
-            QT_ADD(17, t_r2 - t_r1);
             // softmax update against the wave's state
             float s[kNH], mn[kNH];
             bool grow = false;
@@ -447,8 +432,6 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             }
             __builtin_amdgcn_wave_barrier();
 
-            QT_MARK(t_r3);
-            QT_ADD(18, t_r3 - t_r2);
             // values: 16 k-steps of 4 tokens; block b supplies the weights of k-step b
             const h4 pa = *reinterpret_cast<const h4 *>(pr + row * kPrH + 4 * blk4);
             f4 R0 = {0.f, 0.f, 0.f, 0.f}, R1 = {0.f, 0.f, 0.f, 0.f};
@@ -463,19 +446,14 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int h = 0; h < kNH; h++) {
-                O0[h] += R0[h] * (1.0f / vun);             // the state's outputs carry the factor 1/vun
-                O1[h] += R1[h] * (1.0f / vun);
+                O0[h] += R0[h] * inv_vun;                  // the state's outputs carry the factor 1/vun
+                O1[h] += R1[h] * inv_vun;
             }
-            QT_MARK(t_r4);
-            QT_ADD(19, t_r4 - t_r3);
-            QT_ADD(11, 1);
         }
         };
         residual_items(f0, f1, 0);
         {
         // =============================== quantized passes
-        QT_MARK(t_u2);
-        QT_ADD(12, t_u2 - t_u1);
             // this lane's query values: head `row`, the channels of its k-steps, raw and pre-scaled by the
             // 4^-j of the code field (channel pair (c, c+1), c even, is field (c % 16) / 2 of its K word)
             h2 qraw[NKR][2], qscl[NKR][2];
@@ -487,9 +465,34 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                 if (hq < nheads && j0 < j1) bits = *reinterpret_cast<const uint2 *>(a.q + (size_t)(bq0 + hq) * kD + c);
                 qraw[i][0] = as_h2(bits.x);
                 qraw[i][1] = as_h2(bits.y);
+            }
+            // qf: the power of two this lane's head is scaled by (1 on the first attempt; on the second
+            // 2^(14 - E) with E the biased exponent of the head's largest |q|, so that |q| * qf < 1)
+            float qf = 1.0f;
+            if (safe) {
+                typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+                us2 mx2 = {0, 0};
+#pragma unroll
+                for (int i = 0; i < NKR; i++)
+#pragma unroll
+                    for (int ep = 0; ep < 2; ep++)
+                        mx2 = __builtin_elementwise_max(mx2, __builtin_bit_cast(us2, as_u32(qraw[i][ep]) & 0x7fff7fffu));
+                int mx = max((int)mx2[0], (int)mx2[1]);
+                for (int d = 4; d < 64; d <<= 1) mx = max(mx, __shfl_xor(mx, d));   // lanes with the same `row`
+                qf = fast_exp2(14.0f - (float)min(mx >> 10, 30));
+            }
+            float ksc[kNH];                                // kscale / qf of head h (wave-uniform)
+#pragma unroll
+            for (int h = 0; h < NHQ; h++) {
+                const float f = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, qf), PAIRED ? 2 * h : h));
+                ksc[h] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, kscale / f)));
+            }
+#pragma unroll
+            for (int i = 0; i < NKR; i++) {
+                const int c = 4 * (bbk + BGK * i);
 #pragma unroll
                 for (int ep = 0; ep < 2; ep++)
-                    qscl[i][ep] = qraw[i][ep] * (_Float16)fld_scale(((c + 2 * ep) & 15) >> 1);
+                    qscl[i][ep] = qraw[i][ep] * (_Float16)(fld_scale(((c + 2 * ep) & 15) >> 1) * qf);
             }
 
             float s0[kNH], s1[kNH];                        // scores of the lane's two tokens (NHQ heads)
@@ -544,16 +547,16 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                     const float zz[2] = {quad_bcast<0>(qz) * a.c1, quad_bcast<2>(qz) * a.c1};
 #pragma unroll
                     for (int h = 0; h < 2; h++) {
-                        s0[h] = valid ? (acc0[2 * h] + acc0[2 * h + 1]) * kscale + zz[h] : -INFINITY;
-                        s1[h] = valid ? (acc1[2 * h] + acc1[2 * h + 1]) * kscale + zz[h] : -INFINITY;
+                        s0[h] = valid ? (acc0[2 * h] + acc0[2 * h + 1]) * ksc[h] + zz[h] : -INFINITY;
+                        s1[h] = valid ? (acc1[2 * h] + acc1[2 * h + 1]) * ksc[h] + zz[h] : -INFINITY;
                     }
                 } else {
                     const float zz[kNH] = {quad_bcast<0>(qz) * a.c1, quad_bcast<1>(qz) * a.c1,
                                            quad_bcast<2>(qz) * a.c1, quad_bcast<3>(qz) * a.c1};
 #pragma unroll
                     for (int h = 0; h < kNH; h++) {
-                        s0[h] = valid ? acc0[h] * kscale + zz[h] : -INFINITY;
-                        s1[h] = valid ? acc1[h] * kscale + zz[h] : -INFINITY;
+                        s0[h] = valid ? acc0[h] * ksc[h] + zz[h] : -INFINITY;
+                        s1[h] = valid ? acc1[h] * ksc[h] + zz[h] : -INFINITY;
                     }
                 }
             };
@@ -635,8 +638,6 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                 __builtin_amdgcn_wave_barrier();
             };
 
-            QT_MARK(t_p0);
-            QT_ADD(4, t_p0 - t_u2);
             // Loads run one phase ahead of their use and are issued on every path (the last pass requests its
             // own tiles again), so the number in flight is always the same.
             for (int jj = j0; jj < j1; jj++) {
@@ -647,15 +648,12 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                 v_phase(vd, tp);
                 vd = load_v(t2);
             }
-            QT_MARK(t_p1);
-            QT_ADD(5, t_p1 - t_p0);
-            QT_ADD(10, j1 - j0);
         }
         residual_items(b0, b1, 1);
 
         {
-            QT_MARK(t_p1);
             // finish: undo operand scalings, add the zero-point term
+            const float unlg = fast_exp2(-lg);
 #pragma unroll
             for (int h = 0; h < kNH; h++) lsum[h] = l_lane[h] * unlg;
             wave_sum64x4(lsum);
@@ -679,24 +677,31 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                 oa[h] = O0[h] * vun + z0;
                 ob[h] = O1[h] * vun + z1;
             }
-            QT_MARK(t_p2);
-            QT_ADD(6, t_p2 - t_p1);
         }
+        {
+            // any overflowed operand has left an infinity or a NaN in one of the sums
+            float chk = 0.f;
+#pragma unroll
+            for (int h = 0; h < kNH; h++) chk += (O0[h] + O1[h]) + l_lane[h];
+            if (__ballot(!(chk - chk == 0.f)) == 0) break;
+        }
+        }   // attempt
 
         // =============================== publish this wave's partial of the unit
         // the waves that own items of this unit: from the owner of the first item to the owner of the last
         const int wf = wave_of(ib, P, nw_log, inv_p);
         const int wl = wave_of(ib_next - (nb ? kWR : it.nq ? kWQ : kWR), P, nw_log, inv_p);
         const int expected = wl - wf + 1;
-        QT_MARK(t_b0);
+        int lane_p = lane;
+        asm volatile("" : "+v"(lane_p));                   // (opaque copy: address terms computed here, not hoisted)
         if (expected == 1) {
             // the only partial of its unit: normalise and write the result directly
 #pragma unroll
             for (int h = 0; h < kNH; h++) {
                 if (h < nheads) {
                     const float inv = lsum[h] > 0.f ? 1.0f / lsum[h] : 0.f;
-                    a.out[(size_t)(bq0 + h) * kD + lane] = __half_as_ushort(__float2half_rn(oa[h] * inv));
-                    a.out[(size_t)(bq0 + h) * kD + lane + 64] = __half_as_ushort(__float2half_rn(ob[h] * inv));
+                    a.out[(size_t)(bq0 + h) * kD + lane_p] = __half_as_ushort(__float2half_rn(oa[h] * inv));
+                    a.out[(size_t)(bq0 + h) * kD + lane_p + 64] = __half_as_ushort(__float2half_rn(ob[h] * inv));
                 }
             }
         } else {
@@ -708,7 +713,7 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             // hundreds of waves still ends with two short merges, and the first level runs while other
             // waves are still at work.
             constexpr int kSlotB = kNH * kPartialStride * 4, kHeadB = kPartialStride * 4;
-            const int lane8 = lane * 8;
+            const int lane8 = lane_p * 8;
             float M[kNH], L[kNH], Oa[kNH], Ob[kNH];
             // merges `count` partials, `stride` slots apart from slot `first`, into (M, L, Oa, Ob): lane s
             // fetches (max, sum) of partial s, which gives every partial's weight; the output vectors
@@ -772,7 +777,7 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                     if (h >= nheads) continue;
                     const float inv = L[h] > 0.f ? 1.0f / L[h] : 0.f;
                     const h2 r = {(_Float16)(Oa[h] * inv), (_Float16)(Ob[h] * inv)};
-                    *reinterpret_cast<uint32_t *>(a.out + (size_t)(bq0 + h) * kD + 2 * lane) = as_u32(r);
+                    *reinterpret_cast<uint32_t *>(a.out + (size_t)(bq0 + h) * kD + 2 * lane_p) = as_u32(r);
                 }
             };
             auto take_ticket = [&](int *counter) -> int {           // after this wave's stores are acknowledged
@@ -796,11 +801,9 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                 }
             }
             const int old1 = take_ticket(a.cnt1 + slot1);
-            QT_MARK(t_b1);
-            QT_ADD(7, t_b1 - t_b0);
             if (old1 == n1 - 1) {
                 merge(slot1, 1, n1);
-                if (lane == 0) a.cnt1[slot1] = 0;          // ready for the next call
+                if (lane == 0) st_agent_i32(a.cnt1 + slot1, 0);   // ready for the next call
                 if (nsg == 1) {
                     write_out();
                 } else {
@@ -817,24 +820,13 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                     if (old2 == nsg - 1) {
                         merge(wf + 2 * up, 16, nsg);
                         write_out();
-                        if (lane == 0) a.cnt[up] = 0;
+                        if (lane == 0) st_agent_i32(a.cnt + up, 0);
                     }
                 }
-                QT_MARK(t_b2);
-                QT_ADD(21, t_b2 - t_b1);
-                QT_ADD(8, t_b2 - t_b1);
-                QT_ADD(14, 1);
             }
         }
-        QT_ADD(9, 1);
         ib = ib_next;
     }
-#ifdef MINIKV_TIMELINE
-    QT_SET(1, __builtin_amdgcn_s_memrealtime());
-    QT_SET(15, QT_NOW() - t_begin);
-    if (threadIdx.x == 0)
-        for (int i = 0; i < 24; i++) g_qtl[(size_t)(blockIdx.x % 16384) * 24 + i] = qt[i];
-#endif
 }
 
 template <int G, bool LO, bool PAIRED>
@@ -860,9 +852,6 @@ static int launch_stream(DecArgs a, hipStream_t st)
     if (nw > cap_items) nw = cap_items;
     if (nw < 1) nw = 1;
     a.first_slot = resident / 2;
-#ifdef MINIKV_TIMELINE
-    if (const char *e = getenv("MINIKV_NW")) nw = atol(e);
-#endif
     hipLaunchKernelGGL(kern, dim3((unsigned)nw), dim3(64), lds_bytes, st, a);
     return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
 }
@@ -882,11 +871,8 @@ static int launch_stream_g(const DecArgs &a, int G, hipStream_t st)
 int launch_decode_tiled(const DecArgs &a, int G, int units, int variant, hipStream_t st)
 {
     (void)units;
-    switch (variant) {
-    case 3: return a.rep <= 2 ? launch_stream_g<true, true>(a, G, st) : launch_stream_g<true, false>(a, G, st);
-    case 4: return launch_stream_g<false, false>(a, G, st);
-    }
-    return MINIKV_EINVAL;
+    if (variant != 3) return MINIKV_EINVAL;
+    return a.rep <= 2 ? launch_stream_g<true, true>(a, G, st) : launch_stream_g<true, false>(a, G, st);
 }
 
 }  // namespace minikv

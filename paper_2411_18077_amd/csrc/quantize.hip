@@ -23,6 +23,7 @@ struct QuantArgs {
     int32_t *q_len, *r_len;
     int64_t L, idx_stride;
     int Tcap, Rcap, flush;
+    int max_tok;                 // host-side bound of n_tok the launch was sized for
 };
 
 constexpr int kRow = kD + 8;     // LDS row pitch in halfs: 272 B keeps 16-B alignment, staggers banks
@@ -36,7 +37,7 @@ __device__ inline int tokens_to_append(const QuantArgs &a, int u, int &q0)
     int n = a.n_tok[u];
     q0 = a.q_len[u];
     if (a.flush) n = (n == a.Rcap) ? a.Rcap : 0;
-    if (n <= 0 || (n % G) || q0 < 0 || (q0 % G) || q0 + n > a.Tcap || n > a.L) return 0;
+    if (n <= 0 || (n % G) || q0 < 0 || (q0 % G) || q0 + n > a.Tcap || n > a.L || n > a.max_tok) return 0;
     return n;
 }
 
@@ -275,6 +276,7 @@ int launch_quantize(const minikv_shape &s, const minikv_f16 *K, const minikv_f16
     a.Kc = c.Kc; a.Vc = c.Vc; a.Ks = c.Ks; a.Kz = c.Kz; a.Vs = c.Vs; a.Vz = c.Vz;
     a.q_len = c.q_len; a.r_len = c.r_len;
     a.L = L; a.idx_stride = idx_stride; a.Tcap = s.Tcap; a.Rcap = s.Rcap; a.flush = flush ? 1 : 0;
+    a.max_tok = max_tok;
     const int units = s.B * s.Hkv;
     switch (s.G) {
     case 16: return launch_quantize_g<16>(a, units, max_tok, st);

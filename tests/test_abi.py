@@ -19,12 +19,13 @@ def api():
 
 
 def test_exports_every_declared_symbol(api):
-    text = open(os.path.join(ROOT, "include", "minikv.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("minikv.h", "minikv_diag.h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b(minikv_\w+|kv_\w+|selective_flash_attn\w*)\s*\(", text)
     names = sorted(set(names))
     assert {"kv_quantize_pack", "kv_append_residual", "kv_flush_residual", "minikv_decode_attn",
-            "minikv_workspace_bytes", "minikv_buffer_bytes", "minikv_abi_version", "kv_select_hh_rw",
+            "minikv_workspace_bytes", "minikv_buffer_bytes", "minikv_cache_bytes", "minikv_abi_version", "kv_select_hh_rw",
+            "minikv_set_variant", "minikv_stream_read_probe",
             "kv_select_workspace_bytes", "kv_pyramid_budget", "selective_flash_attn",
             "selective_flash_attn_workspace_bytes"} <= set(names)
     l = api.lib()
@@ -41,6 +42,7 @@ def test_buffer_sizes_follow_the_documented_layout(api):
     assert [api.buffer_bytes(s, i) for i in range(10)] == want
     # 64 + 8*D/G bytes per token
     assert sum(want[:6]) == U * 256 * (64 + 8 * 128 // 32)
+    assert [api.cache_bytes(s, i) for i in range(10)] == want
     assert api.workspace_bytes(s) >= 2 * 8 * 2 * 132 * 4
     assert api.buffer_bytes(api.make_shape(1, 1, 1, 64, 32, 128, 0), 0) == 0
 
@@ -76,7 +78,8 @@ def test_pointer_and_workspace_checks(api):
     assert l.kv_quantize_pack(C.byref(s), P(0x1000), P(0x1000), 64, None, 0, P(0x1000), 512, C.byref(good), None) == -1
     assert l.kv_quantize_pack(C.byref(s), P(0x1000), P(0x1000), 64, P(0x1000), 16, P(0x1000), 32, C.byref(good), None) == -1
     assert l.kv_quantize_pack(C.byref(s), P(0x1000), P(0x1000), 64, None, 0, P(0x1000), 0, C.byref(good), None) == 0
-    assert l.minikv_set_variant(99) == -1 and l.minikv_set_variant(2) == -1 and l.minikv_set_variant(0) == 0
+    assert l.minikv_set_variant(99) == -1 and l.minikv_set_variant(2) == -1 and l.minikv_set_variant(4) == -1
+    assert l.minikv_set_variant(0) == 0
     assert b"workspace" in l.minikv_strerror(-3)
 
 
@@ -109,6 +112,10 @@ def test_pyramid_budget_is_host_arithmetic_and_matches_the_oracle(api):
             want = ref.pyramid_budget(n_layers, x, d, bool(bottom_heavy))
             assert len(got) == n_layers
             assert max(abs(a - b) for a, b in zip(got, want)) <= 1e-12 * max(x, 1.0)
+    # values worked by hand (end layers x/d and 2x - x/d, straight line between, mean x)
+    assert api.kv_pyramid_budget(3, 7.0, 7, 1) == [13.0, 7.0, 1.0]
+    assert api.kv_pyramid_budget(3, 7.0, 7, 0) == [1.0, 7.0, 13.0]
+    assert api.kv_pyramid_budget(5, 8.0, 2, 1) == [12.0, 10.0, 8.0, 6.0, 4.0]
     for bad in [(0, 1.0, 7, 1), (4, -1.0, 7, 1), (4, float("nan"), 7, 1), (4, 1.0, 0, 1)]:
         with pytest.raises(api.MinikvError):
             api.kv_pyramid_budget(*bad)

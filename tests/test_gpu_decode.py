@@ -21,7 +21,9 @@ def g():
     return gpu_common
 
 
-def run_both(g, w, r_len, variant, Tcap=None, seed_offset=0, mutate=None):
+def run_both(g, w, r_len, variant, Tcap=None, seed_offset=0, mutate=None, sm=None, prepare=None):
+    """Same seeded inputs through the library and the oracle.  mutate(inp) edits the inputs before the caches
+    are built; prepare(inp, rc) edits them once the oracle's cache (and so its scales) exists."""
     from paper_2411_18077_amd import api
     from oracle import ref
     inp = W.make_inputs(w, "cuda", seed_offset=seed_offset)
@@ -30,17 +32,25 @@ def run_both(g, w, r_len, variant, Tcap=None, seed_offset=0, mutate=None):
     s, rs = g.shapes_for(w, Tcap or inp.Tcap)
     gc = g.gpu_build_cache(inp, s, r_len=r_len)
     rc = g.ref_build_cache(inp, rs, r_len=r_len)
+    if prepare:
+        prepare(inp, rc)
+    sm = g.sm_scale() if sm is None else sm
     out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=torch.float16, device="cuda")
     api.minikv_set_variant(variant)
     try:
-        api.minikv_decode_attn(s, inp.q, gc, g.sm_scale(), out)
+        api.minikv_decode_attn(s, inp.q, gc, sm, out)
         torch.cuda.synchronize()
     finally:
         api.minikv_set_variant(0)
-    want, _, _ = ref.decode_attn(rc, g.to_np(inp.q), g.sm_scale())
+    want, _, _ = ref.decode_attn(rc, g.to_np(inp.q), sm)
     got = g.to_np(out).astype(np.float64)
     assert np.isfinite(got).all()
     return got, want.astype(np.float64)
+
+
+def fp16_step(x):
+    """Spacing of fp16 at |x| (of the normal range; 2^-24 below it)."""
+    return 2.0 ** (np.floor(np.log2(np.maximum(np.abs(x), 2.0 ** -14))) - 10)
 
 
 def tiny(G=32, **kw):
@@ -102,3 +112,87 @@ def test_cfg1_full(g, variant):
     w = W.WORKLOADS[0]
     got, want = run_both(g, w, r_len=w.Rcap, variant=variant)
     assert np.max(np.abs(got - want)) <= TOL
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Head counts the host check accepts: every Hq/Hkv from 1 to 8 (3, 5, 6, 7 leave a set of four query-head
+# rows partly empty, or open a second set with one to three heads) and KV-head counts that are not powers of
+# two (the unit -> batch division by multiplication).  Ragged lengths, residual empty and full.
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("r_full", [False, True])
+@pytest.mark.parametrize("G,Hq,Hkv,B", [(32, 3, 1, 2), (32, 15, 3, 2), (64, 30, 5, 1), (32, 49, 7, 1), (16, 9, 3, 2),
+                                        (32, 6, 1, 3), (128, 35, 5, 1), (32, 21, 7, 2), (32, 8, 1, 1), (64, 5, 5, 3)])
+def test_head_counts_not_a_power_of_two(g, variant, G, Hq, Hkv, B, r_full):
+    w = tiny(G, B=B, Hq=Hq, Hkv=Hkv, L=1024, keep=None, keep_range=(0.1, 1.0), Rcap=max(G, 64), seed=300 + Hq)
+    got, want = run_both(g, w, r_len=w.Rcap if r_full else 0, variant=variant)
+    assert np.max(np.abs(got - want)) <= TOL
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Operand ranges.  The default kernel forms q * Ks and p * Vs in fp16; with its first-choice scalings these
+# stay finite while |q_c * Ks| < 65504 and Vs < 4096 (a V group range below 12288).  Just inside that range
+# the first attempt must hold the tolerance; beyond it the kernel must notice and recompute with normalised
+# operands.  Large values give large outputs, so the bar is 2e-3 or one fp16 step of the oracle's value.
+def _assert_close_in_fp16_steps(got, want, vscale=1.0):
+    # 2e-3 is the bar for values of order one (the weights times V scales are rounded to fp16 once, a relative
+    # error, so for values `vscale` times larger every sum carries `vscale` times the absolute error)
+    tol = np.maximum(TOL * max(1.0, vscale), fp16_step(want))
+    diff = np.abs(got - want)
+    assert np.all(diff <= tol), "max |diff| %g at |o| %g" % (diff.max(), np.abs(want).flat[np.argmax(diff / tol)])
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("vmax", [6000.0, 60000.0])          # V group range <= 12000 (inside) / <= 120000 (far outside)
+@pytest.mark.parametrize("peaked", [False, True])
+def test_value_scales_up_to_the_fp16_range(g, variant, vmax, peaked):
+    w = tiny(32, B=2, Hq=8, Hkv=2, L=1024, keep=0.5, Rcap=32, seed=411)
+
+    def mutate(inp):
+        inp.V.mul_(vmax / 3.0).clamp_(-vmax, vmax)
+        inp.Rv.mul_(vmax / 3.0).clamp_(-vmax, vmax)
+        if peaked:
+            inp.q[0, 0] = inp.K[0, 5] * 2.0
+            inp.q[1, 3] = inp.K[2, 77] * 3.0
+
+    got, want = run_both(g, w, r_len=w.Rcap, variant=variant, mutate=mutate)
+    _assert_close_in_fp16_steps(got, want, vscale=vmax / 3.0)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("target", [6.0e4, 2.4e5, 5.0e5])    # largest |q_c * Ks|: just inside, beyond, far beyond
+@pytest.mark.parametrize("peaked", [False, True])
+def test_query_times_key_scale_up_to_the_fp16_range(g, variant, target, peaked):
+    w = tiny(32, B=1, Hq=4, Hkv=1, L=1024, keep=0.5, Rcap=32, seed=412, n_outlier=3, outlier_scale=8.0)
+    seen = {}
+
+    def prepare(inp, rc):
+        # scale q so that the largest product of a query value and a stored K scale is `target`
+        Ks = rc.Ks.astype(np.float64).reshape(-1, 128)[: int(rc.q_len[0]) // 32]     # [groups, position in row]
+        from oracle import ref
+        perm = ref.k_meta_perm(32)                                                   # channel -> position
+        ks_max = Ks.max(axis=0)[perm]                                                # per channel
+        qa = np.abs(g.to_np(inp.q).astype(np.float64)).reshape(4, 128)
+        f = target / float((qa * ks_max).max())
+        inp.q.mul_(f)
+        assert torch.isfinite(inp.q).all()
+        seen["max"] = float((np.abs(g.to_np(inp.q).astype(np.float64)).reshape(4, 128) * ks_max).max())
+
+    # flat: a softmax scale that brings the (huge) scores back to order one; peaked: the usual scale
+    sm = g.sm_scale() if peaked else g.sm_scale() * 20.0 / target
+    got, want = run_both(g, w, r_len=w.Rcap, variant=variant, prepare=prepare, sm=sm)
+    assert 0.9 * target <= seen["max"] <= 1.01 * target
+    _assert_close_in_fp16_steps(got, want)
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+def test_every_operand_at_the_edge_of_fp16(g, variant):
+    """Keys, values and the query all near +-65504 (scales up to the largest an fp16 group can have)."""
+    w = tiny(32, B=1, Hq=8, Hkv=2, L=512, keep=1.0, Rcap=32, seed=413)
+
+    def mutate(inp):
+        for t in (inp.K, inp.V, inp.Rk, inp.Rv):
+            t.mul_(30000.0).clamp_(-65504.0, 65504.0)
+        inp.q.mul_(20000.0).clamp_(-65504.0, 65504.0)
+
+    got, want = run_both(g, w, r_len=w.Rcap, variant=variant, mutate=mutate, sm=1e-9)
+    _assert_close_in_fp16_steps(got, want, vscale=30000.0)

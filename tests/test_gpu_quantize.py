@@ -83,6 +83,26 @@ def test_refused_units_are_left_unchanged(g):
     assert q[0] == 256 and q[1] == 0 and q[2] == inp.Tcap - 32 and q[3] == 256
 
 
+def test_unit_above_the_host_bound_is_left_unchanged(g):
+    """max_tok sizes the launch; a unit whose device-side n_tok exceeds it must not be half-written with its
+    length bumped: it is left alone, the others match the oracle bit for bit."""
+    from paper_2411_18077_amd import api
+    from oracle import ref
+    w = small(32, L=512, keep=1.0)
+    inp = W.make_inputs(w, "cuda")
+    s, rs = g.shapes_for(w, inp.Tcap)
+    cache = api.Cache(s)
+    n = torch.full_like(inp.n_tok, 128)
+    n[2] = 256                                           # above the bound passed below
+    api.kv_quantize_pack(s, inp.K, inp.V, w.L, None, 0, n, 128, cache)
+    torch.cuda.synchronize()
+    assert cache.q_len.cpu().tolist() == [128, 128, 0, 128]
+    rc = ref.RefCache(rs)
+    n_ref = g.to_np(n).copy(); n_ref[2] = 0              # what the library must have done
+    assert ref.quantize_pack(rc, g.to_np(inp.K), g.to_np(inp.V), n_ref, None) == 0
+    g.assert_cache_bit_exact(cache, rc, what=("Kc", "Ks", "Kz", "Vc", "Vs", "Vz", "q_len"))
+
+
 def test_decode_loop_append_and_flush_bit_exact(g):
     """Algorithm 1 lines 9-15 over 2*n_r + 5 steps on both sides; every buffer equal after every flush."""
     from paper_2411_18077_amd import api
