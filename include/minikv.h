@@ -145,6 +145,22 @@ int minikv_decode_attn(const minikv_shape *shape, const minikv_f16 *q, const min
                        float sm_scale, minikv_f16 *out, void *workspace, size_t workspace_bytes,
                        void *stream);
 
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): minikv_decode_attn with the split-K workspace held in a
+ * device array of the library itself.  Same arguments, same kernel and same result as minikv_decode_attn
+ * without `workspace` / `workspace_bytes`; the call allocates nothing.
+ *   - The array (about 17.3 MB) exists once per GPU from the moment the library is loaded until the process
+ *     ends.  It serves shapes with B * Hkv * ceil(Hq / Hkv / 4) <= minikv_static_workspace_units() (2048);
+ *     larger shapes return MINIKV_EWORKSPACE and launch nothing.
+ *   - Every call on one GPU uses that GPU's array: calls that may overlap on one GPU (different streams without
+ *     an ordering between them) race; order them, or use minikv_decode_attn with a workspace per stream.
+ *   - The first call on a GPU looks up the array's address and enqueues a small kernel on `stream` that
+ *     zero-fills its ticket counters (a kernel, not a memset, so it may be captured); later calls enqueue the
+ *     decode kernel only.  The device that is current at the call must be the one `stream` belongs to. */
+size_t minikv_static_workspace_units(void);
+int minikv_decode_attn_static(const minikv_shape *shape, const minikv_f16 *q, const minikv_cache *cache,
+                              float sm_scale, minikv_f16 *out, void *stream);
+
 /* Section 3.2 (selective flash attention) / Algorithm 1 line 2: causal attention of the prompt with itself that
  * also returns the cumulative attention score of every prompt token, in memory linear in L.  For batch b and
  * query head hq (reading KV head hq / (Hq/Hkv)), with P[i][j] = softmax_j(sm_scale * Q[i].K[j]) over j <= i:

@@ -67,6 +67,10 @@ def lib():
         l.minikv_decode_attn.restype = C.c_int
         l.minikv_decode_attn.argtypes = [C.POINTER(MinikvShape), P, C.POINTER(MinikvCache), C.c_float, P, P,
                                          C.c_size_t, P]
+        l.minikv_decode_attn_static.restype = C.c_int
+        l.minikv_decode_attn_static.argtypes = [C.POINTER(MinikvShape), P, C.POINTER(MinikvCache), C.c_float, P, P]
+        l.minikv_static_workspace_units.restype = C.c_size_t
+        l.minikv_static_workspace_units.argtypes = []
         l.selective_flash_attn.restype = C.c_int
         l.selective_flash_attn.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64, P, P, P, C.c_float, P, P, P, P,
                                            C.c_size_t, P]
@@ -163,6 +167,12 @@ def minikv_decode_attn(shape, q, cache, sm_scale, out, workspace=None, stream=No
     ws = cache.workspace if workspace is None else workspace
     _check(lib().minikv_decode_attn(C.byref(shape), _ptr(q), C.byref(cc), float(sm_scale), _ptr(out), _ptr(ws),
                                     ws.numel() * ws.element_size(), _stream(stream)), "minikv_decode_attn")
+
+
+def minikv_decode_attn_static(shape, q, cache, sm_scale, out, stream=None):
+    cc = cache.c()
+    _check(lib().minikv_decode_attn_static(C.byref(shape), _ptr(q), C.byref(cc), float(sm_scale), _ptr(out),
+                                           _stream(stream)), "minikv_decode_attn_static")
 
 
 def selective_flash_attn_workspace_bytes(B, Hkv, L):

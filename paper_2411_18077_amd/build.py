@@ -15,7 +15,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libminikv.so")
 
-SOURCES = ["api.hip", "quantize.hip", "decode_scalar.hip", "decode_tiled.hip", "select.hip", "prefill_attn.hip"]
+SOURCES = ["api.hip", "quantize.hip", "decode_scalar.hip", "decode_tiled.hip", "decode_static.hip", "select.hip",
+           "prefill_attn.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

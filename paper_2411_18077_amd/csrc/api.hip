@@ -35,9 +35,9 @@ DecodeGeom decode_geom(const minikv_shape &s)
     return g;
 }
 
-static bool aligned16(const void *p) { return p && ((uintptr_t)p & 15u) == 0; }
+bool aligned16(const void *p) { return p && ((uintptr_t)p & 15u) == 0; }
 
-static int validate_cache(const minikv_shape &s, const minikv_cache *c)
+int validate_cache(const minikv_shape &s, const minikv_cache *c)
 {
     if (!c) return MINIKV_EINVAL;
     if (!aligned16(c->Kc) || !aligned16(c->Ks) || !aligned16(c->Kz) || !aligned16(c->Vc) ||

@@ -77,6 +77,13 @@ int launch_append(const minikv_shape &s, const minikv_f16 *k_new, const minikv_f
 int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
                   minikv_f16 *out, void *workspace, int variant, hipStream_t st);
 
+// the same with the three parts of the workspace given one by one: per-unit ticket counters (ws_units ints),
+// sub-group ticket counters (2 * ws_units + kMaxStreamWaves ints), split-K partials
+int launch_decode_parts(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
+                        minikv_f16 *out, int *cnt, int *cnt1, float *partials, int variant, hipStream_t st);
+int validate_cache(const minikv_shape &s, const minikv_cache *c);
+bool aligned16(const void *p);
+
 int launch_prefill(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, const minikv_f16 *Q, const minikv_f16 *K,
                    const minikv_f16 *V, float sm_scale, minikv_f16 *XO, float *lse, float *A_cumul,
                    void *workspace, hipStream_t st);

@@ -191,15 +191,24 @@ int launch_decode_scalar(const DecArgs &a, int G, int units, hipStream_t st)
 int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
                   minikv_f16 *out, void *workspace, int variant, hipStream_t st)
 {
+    int *cnt = reinterpret_cast<int *>(workspace);
+    return launch_decode_parts(s, q, c, sm_scale, out, cnt, cnt + ws_units(s),
+                               reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + ws_counter_bytes(s)),
+                               variant, st);
+}
+
+int launch_decode_parts(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
+                        minikv_f16 *out, int *cnt, int *cnt1, float *partials, int variant, hipStream_t st)
+{
     const DecodeGeom g = decode_geom(s);
     DecArgs a;
     a.q = q; a.Kc = c.Kc; a.Vc = c.Vc; a.Ks = c.Ks; a.Kz = c.Kz; a.Vs = c.Vs; a.Vz = c.Vz;
     a.Rk = c.Rk; a.Rv = c.Rv; a.q_len = c.q_len; a.r_len = c.r_len;
     a.out = out;
     a.first_slot = 0;
-    a.cnt = reinterpret_cast<int *>(workspace);
-    a.cnt1 = a.cnt + ws_units(s);
-    a.ws = reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + ws_counter_bytes(s));
+    a.cnt = cnt;
+    a.cnt1 = cnt1;
+    a.ws = partials;
     a.c1 = sm_scale * 1.44269504088896340736f;
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.rep = g.rep; a.Tcap = s.Tcap; a.Rcap = s.Rcap;
     a.chunk = g.chunk; a.nchunk = g.nchunk;

@@ -138,3 +138,20 @@ def test_prefill_arguments_are_checked_on_the_host(api):
     assert call(2, 4, 2, 100, 0.1, acc=P(0x1004)) == -1
     assert call(2, 4, 2, 100, 0.1, ws=None) == -1
     assert call(2, 4, 2, 100, 0.1, wsb=nws - 1) == -3
+
+
+def test_static_workspace_entry_point_refuses_what_does_not_fit(api):
+    """Host-side checks of minikv_decode_attn_static: nothing is launched and no device is touched."""
+    l = api.lib()
+    cap = int(l.minikv_static_workspace_units())
+    assert cap == 2048
+    P = C.c_void_p
+    cache = api.MinikvCache(*([0x1000] * 10))
+    too_many = api.make_shape(cap + 1, 4, 1, 128, 32, 256, 32)           # cap + 1 units
+    assert l.minikv_decode_attn_static(C.byref(too_many), P(0x1000), C.byref(cache), C.c_float(1.0), P(0x1000), None) == -3
+    two_sets = api.make_shape(cap // 2 + 1, 8, 1, 128, 32, 256, 32)      # two sets of four heads per unit
+    assert l.minikv_decode_attn_static(C.byref(two_sets), P(0x1000), C.byref(cache), C.c_float(1.0), P(0x1000), None) == -3
+    bad = api.make_shape(1, 4, 1, 64, 32, 256, 32)
+    assert l.minikv_decode_attn_static(C.byref(bad), P(0x1000), C.byref(cache), C.c_float(1.0), P(0x1000), None) == -2
+    assert l.minikv_decode_attn_static(C.byref(api.make_shape(1, 4, 1, 128, 32, 256, 32)), None, C.byref(cache),
+                                       C.c_float(1.0), P(0x1000), None) == -1
