@@ -15,6 +15,7 @@ struct DecArgs {
     int *cnt;                    // per-unit ticket counters of the single-launch kernel (zero between calls)
     int *cnt1;                   // ticket counters of the sub-groups, indexed by the sub-group's first slot
     int first_slot;              // workgroups that fill the first wave slot of every SIMD
+    int skew16;                  // sixteenths of a wave pair's range that its first wave takes
     float c1;                    // sm_scale * log2(e): scores are kept in the base-2 domain
     int Hq, Hkv, rep, Tcap, Rcap, chunk, nchunk;
     int units, hsets;            // B*Hkv; sets of 4 query heads per KV head (1 or 2)

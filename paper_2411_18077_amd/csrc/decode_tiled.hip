@@ -51,6 +51,7 @@ namespace minikv {
 // kernel launch does the whole call.  (Drawing passes from a per-unit counter instead was tried: a vector
 // atomic per pass, even one whose result is needed a full pass later, slowed the pass loop by 40 %.)
 struct UnitItems { int nq, nr, T, R; };
+constexpr int kSkew16 = 10;             // share (in sixteenths) of a wave pair's range given to its first wave
 constexpr int kWQ = 2, kWR = 7;        // relative cost of a quantized pass (128 tokens, 12 KB) and a residual
                                        // item (64 fp16 tokens, 32 KB), measured
 
@@ -60,15 +61,23 @@ __device__ inline UnitItems unit_items(const DecArgs &a, int up)
     const int T = clampi(a.q_len[u], 0, a.Tcap), R = clampi(a.r_len[u], 0, a.Rcap);
     return UnitItems{(T + kPass - 1) / kPass, (R + 63) / 64, T, R};
 }
-// P weight units are cut into NW = 2^nw_log ranges [w*P >> nw_log, (w+1)*P >> nw_log).
-__device__ inline long range_start(int w, int P, int nw_log) { return ((long)w * P) >> nw_log; }
-// wave that owns position i: binary32 estimate, then exact correction against the range bounds
-__device__ inline int wave_of(long i, int P, int nw_log, float inv_p)
+// P weight units are cut into NW = 2^nw_log ranges.  Waves 2p and 2p+1 share the pair range
+// [p*2P >> nw_log, (p+1)*2P >> nw_log); the first of them takes skew16/16 of it (8 = equal halves).
+__device__ inline long range_start(int w, int P, int nw_log, int skew16)
 {
-    int w = (int)((float)i * (float)(1 << nw_log) * inv_p);
+    if (nw_log == 0) return w ? P : 0;
+    const long s0 = ((long)(w >> 1) * P) >> (nw_log - 1);
+    if (!(w & 1)) return s0;
+    const long s1 = ((long)((w >> 1) + 1) * P) >> (nw_log - 1);
+    return s0 + (((s1 - s0) * skew16) >> 4);
+}
+// wave that owns position i: binary32 estimate, then exact correction against the range bounds
+__device__ inline int wave_of(long i, int P, int nw_log, float inv_p, int skew16)
+{
+    int w = (int)((float)i * inv_p);                       // inv_p = NW / P
     w = min(max(w, 0), (1 << nw_log) - 1);
-    while (range_start(w, P, nw_log) > i) w--;
-    while (range_start(w + 1, P, nw_log) <= i) w++;
+    while (range_start(w, P, nw_log, skew16) > i) w--;
+    while (range_start(w + 1, P, nw_log, skew16) <= i) w++;
     return w;
 }
 
@@ -185,8 +194,13 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
     const bool paired = NW == 2 * a.first_slot;
     const int w = !paired ? (int)blockIdx.x
                 : (int)blockIdx.x < a.first_slot ? 2 * (int)blockIdx.x : 2 * ((int)blockIdx.x - a.first_slot) + 1;
-    const long start = range_start(w, P, nw_log), end = range_start(w + 1, P, nw_log);
-    const float inv_p = 1.0f / (float)P;
+    // (the wave in the first slot of a SIMD runs faster; both parts of a pair range must stay longer than one
+    // item, so that every wave between the first and the last of a unit owns an item of it)
+    const int want16 = min(max(a.skew16, 4), 12);
+    const int skew16 = paired && ((((2L * P) >> nw_log) * min(want16, 16 - want16)) >> 4) >= kWR ? want16 : 8;
+    const long start = range_start(w, P, nw_log, skew16), end = range_start(w + 1, P, nw_log, skew16);
+    // (NW / P as a wave-uniform value in a scalar register)
+    const float inv_p = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, (float)NW / (float)P)));
 
     // ---------------- the unit whose weight span holds position `start`
     int up = -1;
@@ -256,6 +270,10 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
         const int bq0 = bi * a.Hq + (u - bi * a.Hkv) * a.rep + hs * kNH;
         const int nheads = min(kNH, a.rep - hs * kNH);
         const int t_end = it.T;
+        // the waves that own items of this unit: from the owner of the first item to the owner of the last
+        const int wf = wave_of(ib, P, nw_log, inv_p, skew16);
+        const int wl = wave_of(ib_next - (nb ? kWR : it.nq ? kWQ : kWR), P, nw_log, inv_p, skew16);
+        const int expected = wl - wf + 1;
         const uint32_t *Kc = a.Kc + (size_t)u * kc_words(a.Tcap);
         const uint32_t *Vc = a.Vc + (size_t)u * vc_words(a.Tcap);
         const uint16_t *Ks = a.Ks + (size_t)u * (a.Tcap / G) * kD;
@@ -266,31 +284,45 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
         int lane_u = lane;
         asm volatile("" : "+v"(lane_u));                   // (opaque copy: per-lane load offsets are set up per unit)
         const int bbk_u = (lane_u >> 2) % BGK;
-        auto load_k = [&](int tp) -> KD {
-            KD d;
-            const u4 *ktile = reinterpret_cast<const u4 *>(Kc + (size_t)(tp >> 7) * 1024);
-#pragma unroll
-            for (int i = 0; i < 4; i++) d.kw[i] = ktile[i * 64 + lane];
+        // Loaders of one pass's tiles, in the pieces the phases consume them in (each piece is requested again,
+        // for the wave's next pass, as soon as its registers have been read for the last time: every piece is
+        // then in flight for about a whole pass, which is what keeps enough bytes outstanding per wave).
+        auto load_k_meta = [&](KD &d, int tp) {
             const bool gvalid = tp + gl * G < t_end;
             const size_t go = ((size_t)(tp / G) + (gvalid ? gl : 0)) * kD + bbk_u * (NKR * 4);
             d.ks = load_words<NKW>(Ks + go);
             d.kz = load_words<NKW>(Kz + go);
+        };
+        auto load_k_codes = [&](KD &d, int tp, int half) {       // half 0: words 0..3 of both tokens, 1: words 4..7
+            const u4 *ktile = reinterpret_cast<const u4 *>(Kc + (size_t)(tp >> 7) * 1024);
+            d.kw[half] = ktile[half * 64 + lane_u];
+            d.kw[2 + half] = ktile[(2 + half) * 64 + lane_u];
+        };
+        auto load_v_meta = [&](VD &d, int tp) {
+            // past the end the (clamped) load still happens (the weights of those tokens are zero), so that the
+            // number of loads in flight is the same on every path
+            const bool valid = tp + 2 * lane_u < t_end;
+            const size_t vo = (size_t)(valid ? tp + 2 * lane_u : tp) * NCG;
+            d.vs = load_words<NCG>(Vs + vo);
+            d.vz = load_words<NCG>(Vz + vo);
+        };
+        auto load_v_codes = [&](VD &d, int tp, int tl) {         // tl: 64-token tile of the pass
+            const u4 *vtile = reinterpret_cast<const u4 *>(Vc + (size_t)(tp >> 6) * (4 * kD));
+            d.vw[0][tl] = vtile[tl * kD + lane_u];
+            d.vw[1][tl] = vtile[tl * kD + lane_u + 64];
+        };
+        auto load_k = [&](int tp) -> KD {
+            KD d;
+            load_k_codes(d, tp, 0);
+            load_k_codes(d, tp, 1);
+            load_k_meta(d, tp);
             return d;
         };
         auto load_v = [&](int tp) -> VD {
             VD d;
-            const u4 *vtile = reinterpret_cast<const u4 *>(Vc + (size_t)(tp >> 6) * (4 * kD));
-#pragma unroll
-            for (int tl = 0; tl < 2; tl++) {
-                d.vw[0][tl] = vtile[tl * kD + lane];
-                d.vw[1][tl] = vtile[tl * kD + lane + 64];
-            }
-            // past the end the (clamped) load still happens and the value is masked to zero afterwards,
-            // so that the number of loads in flight is the same on every path
-            const bool valid = tp + 2 * lane < t_end;
-            const size_t vo = (size_t)(valid ? tp + 2 * lane : tp) * NCG;
-            d.vs = load_words<NCG>(Vs + vo);
-            d.vz = load_words<NCG>(Vz + vo);
+            load_v_codes(d, tp, 0);
+            load_v_codes(d, tp, 1);
+            load_v_meta(d, tp);
             return d;
         };
 
@@ -313,9 +345,26 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
         const float lg = hd - (float)fld_shift(lane & 7);
         const float vun = safe ? 33554432.0f : 1048576.0f; // 2^24 (subnormal fields) / 2^hd (ps headroom)
         const float inv_vun = 1.0f / vun;
-        // The tiles of the first pass are requested before anything else is waited for.
+        // This lane's query values for the quantized passes (head `row`, the channels of its k-steps).
+        h2 qraw[NKR][2];
+        auto load_q = [&]() {
+#pragma unroll
+            for (int i = 0; i < NKR; i++) {
+                const int c = 4 * (bbk_u + BGK * i);
+                uint2 bits = {0u, 0u};
+                const int hq = PAIRED ? (lane_u & 3) >> 1 : (lane_u & 3);   // the head whose A rows this lane supplies
+                if (hq < nheads && j0 < j1) bits = *reinterpret_cast<const uint2 *>(a.q + (size_t)(bq0 + hq) * kD + c);
+                qraw[i][0] = as_h2(bits.x);
+                qraw[i][1] = as_h2(bits.y);
+            }
+        };
+        // The tiles of the first pass are requested before anything else is waited for; without residual items
+        // in front the query values go first (they are needed first, and a wait for them then does not wait
+        // for the tiles), with residual items they are fetched afterwards (fewer registers live in between).
         KD kd = {};
         VD vd = {};
+        const bool front = f0 < f1;
+        if (!front) load_q();
         if (j0 < j1) {
             kd = load_k(j0 * kPass);
             vd = load_v(j0 * kPass);
@@ -367,7 +416,7 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
 #pragma unroll
             for (int i = 0; i < 2; i++) {
                 uint2 bits = {0u, 0u};
-                if (row < nheads) bits = *reinterpret_cast<const uint2 *>(a.q + (size_t)(bq0 + row) * kD + 4 * (blk4 + 16 * i));
+                if ((lane_r & 3) < nheads) bits = *reinterpret_cast<const uint2 *>(a.q + (size_t)(bq0 + (lane_r & 3)) * kD + 4 * ((lane_r >> 2) + 16 * i));
                 const h2 lo = as_h2(bits.x), hi = as_h2(bits.y);
                 qa[i] = h4{lo[0], lo[1], hi[0], hi[1]};
             }
@@ -451,21 +500,15 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             }
         }
         };
-        residual_items(f0, f1, 0);
+        if (front) {
+            residual_items(f0, f1, 0);
+            load_q();
+        }
         {
         // =============================== quantized passes
-            // this lane's query values: head `row`, the channels of its k-steps, raw and pre-scaled by the
-            // 4^-j of the code field (channel pair (c, c+1), c even, is field (c % 16) / 2 of its K word)
-            h2 qraw[NKR][2], qscl[NKR][2];
-#pragma unroll
-            for (int i = 0; i < NKR; i++) {
-                const int c = 4 * (bbk + BGK * i);
-                uint2 bits = {0u, 0u};
-                const int hq = PAIRED ? row >> 1 : row;    // the head whose A rows this lane supplies
-                if (hq < nheads && j0 < j1) bits = *reinterpret_cast<const uint2 *>(a.q + (size_t)(bq0 + hq) * kD + c);
-                qraw[i][0] = as_h2(bits.x);
-                qraw[i][1] = as_h2(bits.y);
-            }
+            // the query values pre-scaled by the 4^-j of the code field (channel pair (c, c+1), c even, is field
+            // (c % 16) / 2 of its K word)
+            h2 qscl[NKR][2];
             // qf: the power of two this lane's head is scaled by (1 on the first attempt; on the second
             // 2^(14 - E) with E the biased exponent of the head's largest |q|, so that |q| * qf < 1)
             float qf = 1.0f;
@@ -498,7 +541,7 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             float s0[kNH], s1[kNH];                        // scores of the lane's two tokens (NHQ heads)
 
             // ---------------- K phase: scores of tokens 2*lane, 2*lane+1 for the 4 heads
-            auto k_phase = [&](const KD &d, int tp) {
+            auto k_phase = [&](KD &d, int tp, int t2) {        // t2: the pass whose tiles are requested meanwhile
                 const bool valid = tp + 2 * lane < t_end;  // both tokens of the lane (t_end % 16 == 0)
                 // A operands of this lane's k-steps (exact hi + lo split of q * Ks), qz = sum_c q_c Kz[g,c]
                 h4 a_hi[NKR], a_lo[NKR];
@@ -521,6 +564,9 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                         if constexpr (LO) a_lo[i] = h4{lo[0][0], lo[0][1], lo[1][0], lo[1][1]};
                     }
                 }
+                __builtin_amdgcn_sched_barrier(0);         // (all A operands first: the rows are then free)
+                load_k_meta(d, t2);                        // the scale / zero rows have been consumed
+                __builtin_amdgcn_sched_barrier(0);
                 // sum the partial qz of the BGK blocks of the group (same row, lanes 4 apart)
                 if constexpr (BGK == 2) qz += __shfl_xor(qz, 4);
                 if constexpr (BGK >= 4) { qz = dpp_ror_add<4>(qz); qz = dpp_ror_add<8>(qz); }
@@ -542,7 +588,15 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                         mfma_k<CBK>(acc0, acc1, a_hi[s / BGK], b0, b1, s % BGK);
                         if constexpr (LO && !PAIRED) mfma_k<CBK>(acc0, acc1, a_lo[s / BGK], b0, b1, s % BGK);
                     }
+                    if (wd == 3) {                         // words 0..3 are done
+                        __builtin_amdgcn_sched_barrier(0);
+                        load_k_codes(d, t2, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
+                __builtin_amdgcn_sched_barrier(0);
+                load_k_codes(d, t2, 1);
+                __builtin_amdgcn_sched_barrier(0);
                 if constexpr (PAIRED) {
                     const float zz[2] = {quad_bcast<0>(qz) * a.c1, quad_bcast<2>(qz) * a.c1};
 #pragma unroll
@@ -562,7 +616,7 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             };
 
             // ---------------- softmax update, ps table, V products
-            auto v_phase = [&](const VD &d, int tp) {
+            auto v_phase = [&](VD &d, int tp, int t2) {
                 const bool valid = tp + 2 * lane < t_end;
                 float mn[kNH];
                 bool grow = false;
@@ -598,6 +652,9 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                         vsp[g] = as_h2(valid ? sv : 0u);
                         vzp[g] = as_h2(valid ? zv : 0u);
                     }
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_v_meta(d, t2);                    // the scales and zero-points have been consumed
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int h = 0; h < NHQ; h++) {
                         const float mo = m[h] - lg;
@@ -634,19 +691,25 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                         const h4 b1 = {x10[0], x10[1], x11[0], x11[1]};
                         mfma_v<CBV>(O0, O1, a0[ks / BGV], a1[ks / BGV], b0, b1, ks % BGV);
                     }
+                    if (blk == 3) {                        // the first 64-token tile is done
+                        __builtin_amdgcn_sched_barrier(0);
+                        load_v_codes(d, t2, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
+                __builtin_amdgcn_sched_barrier(0);
+                load_v_codes(d, t2, 1);
                 __builtin_amdgcn_wave_barrier();
             };
 
-            // Loads run one phase ahead of their use and are issued on every path (the last pass requests its
-            // own tiles again), so the number in flight is always the same.
+            // Every piece of a pass's tiles is requested for the next pass right after its last use and is
+            // issued on every path (the last pass requests its own tiles again), so the number in flight is
+            // always the same.
             for (int jj = j0; jj < j1; jj++) {
                 const int tp = jj * kPass;
                 const int t2 = (jj + 1 < j1 ? jj + 1 : jj) * kPass;
-                k_phase(kd, tp);
-                kd = load_k(t2);
-                v_phase(vd, tp);
-                vd = load_v(t2);
+                k_phase(kd, tp, t2);
+                v_phase(vd, tp, t2);
             }
         }
         residual_items(b0, b1, 1);
@@ -688,10 +751,6 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
         }   // attempt
 
         // =============================== publish this wave's partial of the unit
-        // the waves that own items of this unit: from the owner of the first item to the owner of the last
-        const int wf = wave_of(ib, P, nw_log, inv_p);
-        const int wl = wave_of(ib_next - (nb ? kWR : it.nq ? kWQ : kWR), P, nw_log, inv_p);
-        const int expected = wl - wf + 1;
         int lane_p = lane;
         asm volatile("" : "+v"(lane_p));                   // (opaque copy: address terms computed here, not hoisted)
         if (expected == 1) {
@@ -852,6 +911,7 @@ static int launch_stream(DecArgs a, hipStream_t st)
     if (nw > cap_items) nw = cap_items;
     if (nw < 1) nw = 1;
     a.first_slot = resident / 2;
+    a.skew16 = kSkew16;
     hipLaunchKernelGGL(kern, dim3((unsigned)nw), dim3(64), lds_bytes, st, a);
     return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
 }
