@@ -3,7 +3,8 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "minikv_ref.c")
+SRCS = [os.path.join(HERE, f) for f in ("minikv_ref.c", "minikv_pt_ref.c")]
+HDRS = [os.path.join(HERE, f) for f in ("minikv_ref.h", "minikv_pt_ref.h")]
 LIB = os.path.join(HERE, "libminikv_ref.so")
 
 # -ffp-contract=off and no fast-math: the code decisions are individually rounded binary32 operations.
@@ -12,10 +13,9 @@ FLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "
 
 
 def build(force=False):
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(
-            os.path.getmtime(SRC), os.path.getmtime(os.path.join(HERE, "minikv_ref.h"))):
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(os.path.getmtime(f) for f in SRCS + HDRS):
         return LIB
-    subprocess.check_call(["gcc", *FLAGS, SRC, "-o", LIB, "-lm"])
+    subprocess.check_call(["gcc", *FLAGS, *SRCS, "-o", LIB, "-lm"])
     return LIB
 
 

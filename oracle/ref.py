@@ -38,8 +38,11 @@ def lib():
         for name in ("ref_check_shape", "kv_quantize_pack_ref", "kv_append_residual_ref",
                      "kv_flush_residual_ref", "minikv_decode_attn_ref", "ref_unpack_codes", "ref_dequant",
                      "ref_k_meta_pos", "kv_select_hh_rw_ref", "kv_pyramid_budget_ref",
-                     "selective_flash_attn_ref"):
+                     "selective_flash_attn_ref", "ref_pt_check_shape", "kv_quantize_pack_pt_ref",
+                     "minikv_decode_attn_pt_ref", "ref_pt_unpack_codes"):
             getattr(_lib, name).restype = C.c_int
+        _lib.ref_pt_token_bytes.restype = C.c_size_t
+        _lib.ref_pt_token_bytes.argtypes = [C.c_int, C.c_int, C.c_int]
     return _lib
 
 
@@ -220,3 +223,86 @@ def f64_to_f16_bits(x):
 
 def f16_bits_to_f32(h):
     return float(lib().ref_f16_to_f32(C.c_uint16(h)))
+
+
+# ---------------------------------------------------------------------------------------------------------
+# per-token quantized cache (oracle/minikv_pt_ref.c)
+
+class _PtShape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "D", "G", "bits", "Tcap")]
+
+
+class _PtCache(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("Kc", "Ks", "Kz", "Vc", "Vs", "Vz", "q_len")]
+
+
+class RefPtShape:
+    def __init__(self, B, Hq, Hkv, D, G, bits, Tcap):
+        self.B, self.Hq, self.Hkv, self.D, self.G, self.bits, self.Tcap = B, Hq, Hkv, D, G, bits, Tcap
+
+    @property
+    def units(self):
+        return self.B * self.Hkv
+
+    def c(self):
+        return _PtShape(self.B, self.Hq, self.Hkv, self.D, self.G, self.bits, self.Tcap)
+
+    def check(self):
+        return lib().ref_pt_check_shape(C.byref(self.c()))
+
+
+class RefPtCache:
+    """Host buffers of one per-token quantized cache, zero-initialised (storage order: minikv_pt_ref.h)."""
+
+    def __init__(self, s: RefPtShape):
+        U, D, G, T, b = s.units, s.D, s.G, s.Tcap, s.bits
+        self.shape = s
+        self.Kc = np.zeros((U, T * D * b // 32), np.uint32)
+        self.Vc = np.zeros((U, T * D * b // 32), np.uint32)
+        self.Ks = np.zeros((U, T, D // G), np.float16)
+        self.Kz = np.zeros((U, T, D // G), np.float16)
+        self.Vs = np.zeros((U, T, D // G), np.float16)
+        self.Vz = np.zeros((U, T, D // G), np.float16)
+        self.q_len = np.zeros((U,), np.int32)
+
+    def c(self):
+        return _PtCache(*(a.ctypes.data for a in (self.Kc, self.Ks, self.Kz, self.Vc, self.Vs, self.Vz, self.q_len)))
+
+
+def pt_token_bytes(D, G, bits):
+    return int(lib().ref_pt_token_bytes(D, G, bits))
+
+
+def quantize_pack_pt(cache: RefPtCache, K, V, n_tok, idx=None):
+    s = cache.shape
+    K, V = _f16(K), _f16(V)
+    n_tok = np.ascontiguousarray(n_tok, np.int32)
+    stride = 0
+    if idx is not None:
+        idx = np.ascontiguousarray(idx, np.int32)
+        stride = idx.shape[1]
+    cc = cache.c()
+    return lib().kv_quantize_pack_pt_ref(C.byref(s.c()), _p(K), _p(V), C.c_int64(K.shape[1]), _p(idx),
+                                         C.c_int64(stride), _p(n_tok), C.byref(cc))
+
+
+def decode_attn_pt(cache: RefPtCache, q, sm_scale):
+    """q float16 [B, Hq, D] -> (out float16, out float64)."""
+    s = cache.shape
+    q = _f16(q)
+    out16 = np.zeros((s.B, s.Hq, s.D), np.float16)
+    out64 = np.zeros((s.B, s.Hq, s.D), np.float64)
+    cc = cache.c()
+    rc = lib().minikv_decode_attn_pt_ref(C.byref(s.c()), _p(q), C.byref(cc), C.c_float(sm_scale), _p(out16), _p(out64))
+    assert rc == 0
+    return out16, out64
+
+
+def unpack_codes_pt(cache: RefPtCache, unit):
+    s = cache.shape
+    T = int(cache.q_len[unit])
+    kc = np.zeros((max(T, 1), s.D), np.uint8)
+    vc = np.zeros((max(T, 1), s.D), np.uint8)
+    cc = cache.c()
+    assert lib().ref_pt_unpack_codes(C.byref(s.c()), C.byref(cc), int(unit), _p(kc), _p(vc)) == 0
+    return kc[:T], vc[:T]
