@@ -161,6 +161,50 @@ size_t minikv_static_workspace_units(void);
 int minikv_decode_attn_static(const minikv_shape *shape, const minikv_f16 *q, const minikv_cache *cache,
                               float sm_scale, minikv_f16 *out, void *stream);
 
+/* ---------------------------------------------------------------------------------------------------------
+ * Variant: PER-TOKEN quantized cache.  The paper's appendix on token-wise quantization quantizes keys and
+ * values per token with 8, 4 and 2 bits (2 bits is the case it reports as failing, the reason MiniKV groups
+ * keys per channel, Section 3.1.1), and its 4-bit per-token baseline is the one whose size the appendix on KV
+ * cache compression ratios works out (16-bit values against 4-bit codes plus a 16-bit scale and zero-point per
+ * head: a factor 3.76 at head dimension 128, i.e. bits = 4, G = 128 here).  These two calls build and read such
+ * a cache, for comparisons against the 2-bit per-channel path above; there is no residual buffer (a token can
+ * be quantized the moment it exists).
+ *
+ * Quantizer: as above with 2^bits - 1 steps, the G channels of ONE token forming a group, for K and V alike.
+ * Shape rules: D == 128; G in {32, 64, 128}; bits in {2, 4, 8}; Tcap > 0, Tcap % 64 == 0; Hq % Hkv == 0,
+ * Hq / Hkv <= 8.  Storage (per unit; cpw = 32 / bits codes per word, code i of a word at bits
+ * [bits*i, bits*i + bits)):
+ *   Kc uint32 [Tcap][D/cpw]  token major: word w of token t holds channels cpw*w ..
+ *   Vc uint32 [Tcap/cpw][D]  channel major: word (t/cpw, c) holds cpw consecutive tokens of channel c
+ *   Ks, Kz, Vs, Vz fp16 [Tcap][D/G];  q_len int32 [B*Hkv], a multiple of 16.
+ * minikv_pt_cache_bytes takes the minikv_buffer index of a buffer (the residual entries give 0). */
+typedef struct minikv_pt_shape {
+    int32_t B, Hq, Hkv, D, G, bits, Tcap;
+} minikv_pt_shape;
+
+typedef struct minikv_pt_cache {
+    uint32_t   *Kc;
+    minikv_f16 *Ks, *Kz;
+    uint32_t   *Vc;
+    minikv_f16 *Vs, *Vz;
+    int32_t    *q_len;
+} minikv_pt_cache;
+
+size_t minikv_pt_cache_bytes(const minikv_pt_shape *shape, int which);
+size_t minikv_pt_workspace_bytes(const minikv_pt_shape *shape);
+
+/* As kv_quantize_pack, per token: n_tok[u] rows (a multiple of 16, <= max_tok) are quantized and appended at
+ * q_len[u] (a multiple of 16); a unit that breaks a rule is left unchanged. */
+int kv_quantize_pack_pt(const minikv_pt_shape *shape, const minikv_f16 *K, const minikv_f16 *V, int64_t L,
+                        const int32_t *idx, int64_t idx_stride, const int32_t *n_tok, int32_t max_tok,
+                        minikv_pt_cache *cache, void *stream);
+
+/* out[b][hq] = softmax(sm_scale * q[b][hq] . K_hat^T) . V_hat (Appendix A eq. (1) on the dequantized cache)
+ * over the q_len[u] tokens of unit u, fp32 accumulation, fp16 result; a unit without tokens gives zeros.
+ * workspace: at least minikv_pt_workspace_bytes(shape) bytes, 16-byte aligned, no initial state required. */
+int minikv_decode_attn_pt(const minikv_pt_shape *shape, const minikv_f16 *q, const minikv_pt_cache *cache,
+                          float sm_scale, minikv_f16 *out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Section 3.2 (selective flash attention) / Algorithm 1 line 2: causal attention of the prompt with itself that
  * also returns the cumulative attention score of every prompt token, in memory linear in L.  For batch b and
  * query head hq (reading KV head hq / (Hq/Hkv)), with P[i][j] = softmax_j(sm_scale * Q[i].K[j]) over j <= i:

@@ -26,6 +26,17 @@ class MinikvCache(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in BUF_NAMES]
 
 
+class MinikvPtShape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "D", "G", "bits", "Tcap")]
+
+
+PT_BUF_NAMES = ("Kc", "Ks", "Kz", "Vc", "Vs", "Vz", "q_len")
+
+
+class MinikvPtCache(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in PT_BUF_NAMES]
+
+
 class MinikvError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -71,6 +82,16 @@ def lib():
         l.minikv_decode_attn_static.argtypes = [C.POINTER(MinikvShape), P, C.POINTER(MinikvCache), C.c_float, P, P]
         l.minikv_static_workspace_units.restype = C.c_size_t
         l.minikv_static_workspace_units.argtypes = []
+        l.minikv_pt_cache_bytes.restype = C.c_size_t
+        l.minikv_pt_cache_bytes.argtypes = [C.POINTER(MinikvPtShape), C.c_int]
+        l.minikv_pt_workspace_bytes.restype = C.c_size_t
+        l.minikv_pt_workspace_bytes.argtypes = [C.POINTER(MinikvPtShape)]
+        l.kv_quantize_pack_pt.restype = C.c_int
+        l.kv_quantize_pack_pt.argtypes = [C.POINTER(MinikvPtShape), P, P, C.c_int64, P, C.c_int64, P, C.c_int32,
+                                          C.POINTER(MinikvPtCache), P]
+        l.minikv_decode_attn_pt.restype = C.c_int
+        l.minikv_decode_attn_pt.argtypes = [C.POINTER(MinikvPtShape), P, C.POINTER(MinikvPtCache), C.c_float, P, P,
+                                            C.c_size_t, P]
         l.selective_flash_attn.restype = C.c_int
         l.selective_flash_attn.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int64, P, P, P, C.c_float, P, P, P, P,
                                            C.c_size_t, P]
@@ -210,3 +231,49 @@ def minikv_stream_read_probe(src, sums, stream=None):
 
 def minikv_set_variant(v):
     _check(lib().minikv_set_variant(int(v)), "minikv_set_variant")
+
+
+# ---------------------------------------------------------------------------------------------------------
+# per-token quantized variant
+
+def make_pt_shape(B, Hq, Hkv, D, G, bits, Tcap):
+    return MinikvPtShape(B, Hq, Hkv, D, G, bits, Tcap)
+
+
+class PtCache:
+    """Caller-owned device buffers of one per-token quantized cache, sized by minikv_pt_cache_bytes."""
+
+    def __init__(self, shape, device="cuda"):
+        self.shape = shape
+        self.t = {}
+        for name in PT_BUF_NAMES:
+            nbytes = int(lib().minikv_pt_cache_bytes(C.byref(shape), BUF_NAMES.index(name)))
+            dt = _BUF_DTYPE[name]
+            self.t[name] = torch.zeros(max(nbytes // dt.itemsize, 1), dtype=dt, device=device)
+        self.workspace = torch.empty(max(int(lib().minikv_pt_workspace_bytes(C.byref(shape))), 16), dtype=torch.uint8,
+                                     device=device)
+
+    def __getattr__(self, name):
+        t = self.__dict__.get("t", {})
+        if name in t:
+            return t[name]
+        raise AttributeError(name)
+
+    def c(self):
+        return MinikvPtCache(*(self.t[n].data_ptr() for n in PT_BUF_NAMES))
+
+    def nbytes(self):
+        return sum(v.numel() * v.element_size() for v in self.t.values())
+
+
+def kv_quantize_pack_pt(shape, K, V, L, idx, idx_stride, n_tok, max_tok, cache, stream=None):
+    cc = cache.c()
+    _check(lib().kv_quantize_pack_pt(C.byref(shape), _ptr(K), _ptr(V), int(L), _ptr(idx), int(idx_stride),
+                                     _ptr(n_tok), int(max_tok), C.byref(cc), _stream(stream)), "kv_quantize_pack_pt")
+
+
+def minikv_decode_attn_pt(shape, q, cache, sm_scale, out, stream=None):
+    cc = cache.c()
+    ws = cache.workspace
+    _check(lib().minikv_decode_attn_pt(C.byref(shape), _ptr(q), C.byref(cc), float(sm_scale), _ptr(out), _ptr(ws),
+                                       ws.numel(), _stream(stream)), "minikv_decode_attn_pt")

@@ -16,7 +16,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libminikv.so")
 
 SOURCES = ["api.hip", "quantize.hip", "decode_scalar.hip", "decode_tiled.hip", "decode_static.hip", "select.hip",
-           "prefill_attn.hip"]
+           "prefill_attn.hip", "pt.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -26,7 +26,7 @@ FLAGS = [
     "-Wall", "-Wno-unused-function",
 ]
 # per-file extras: the quantizer's code decisions are individually rounded binary32 operations
-EXTRA = {"quantize.hip": ["-ffp-contract=off"]}
+EXTRA = {"quantize.hip": ["-ffp-contract=off"], "pt.hip": ["-ffp-contract=off"]}
 
 
 def hipcc():

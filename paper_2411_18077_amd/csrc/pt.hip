@@ -1,0 +1,521 @@
+// Per-token quantized KV cache: the token-wise quantization the paper's appendix studies (8, 4 and 2 bits for
+// keys and values alike; 2 bits is the case it reports as failing) and its 4-bit baseline, whose size the
+// appendix on KV cache compression ratios works out.  Keys are quantized like values: the G channels of one
+// token share a zero-point and a scale.  Entry points: kv_quantize_pack_pt, minikv_decode_attn_pt.
+//
+// Storage (per unit; cpw = 32 / bits codes per word, code i of a word at bits [bits*i, bits*i + bits)):
+//   Kc [Tcap][D/cpw]   token major (a token's codes are contiguous: the score phase has one token per thread)
+//   Vc [Tcap/cpw][D]   channel major (a word = cpw consecutive tokens of one channel: the value phase has one
+//                      channel per thread and consecutive threads read consecutive words)
+//   Ks, Kz, Vs, Vz fp16 [Tcap][D/G];  q_len int32, a multiple of 16.
+#include "common.h"
+
+#include <hip/hip_fp16.h>
+
+namespace minikv {
+
+constexpr int kPtBlockTok = 64;      // tokens one workgroup of the quantizer takes
+constexpr int kPtSB = 256;           // tokens per inner block of the decode kernel (= threads)
+constexpr int kPtMaxRep = 8;
+
+struct PtQuantArgs {
+    const uint16_t *K, *V;
+    const int32_t *idx, *n_tok;
+    uint32_t *Kc, *Vc;
+    uint16_t *Ks, *Kz, *Vs, *Vz;
+    int32_t *q_len;
+    int64_t L, idx_stride;
+    int Tcap, max_tok;
+};
+
+__device__ inline float pt_h2f(uint16_t h) { return __half2float(__ushort_as_half(h)); }
+
+// Tokens this unit appends, or 0 when the request is not a positive multiple of 16 that fits.
+__device__ inline int pt_tokens_to_append(const PtQuantArgs &a, int u, int &q0)
+{
+    const int n = a.n_tok[u];
+    q0 = a.q_len[u];
+    if (n <= 0 || (n & 15) || q0 < 0 || (q0 & 15) || q0 + n > a.Tcap || n > a.L || n > a.max_tok) return 0;
+    return n;
+}
+
+// The quantizer of one group: zero = min (fp16, -0 stored as +0), scale = fp16((max - min) / levels) in
+// binary32, 1/scale of the STORED scale; every operation separately rounded (this file is compiled without
+// floating-point contraction).
+__device__ inline void pt_group_params(float mn, float mx, float levels, uint16_t &sh, uint16_t &zh, float &inv, float &zf)
+{
+    zh = __half_as_ushort(__float2half_rn(mn));
+    if ((zh & 0x7fffu) == 0) zh = 0;
+    zf = pt_h2f(zh);
+    const float range = mx - mn;
+    const float step = range / levels;
+    const __half s = __float2half_rn(step);
+    sh = __half_as_ushort(s);
+    const float sf = __half2float(s);
+    inv = (sf == 0.0f) ? 0.0f : 1.0f / sf;
+}
+__device__ inline uint32_t pt_code(float x, float zf, float inv, float levels)
+{
+    const float d = x - zf;
+    const float u = d * inv;
+    return (uint32_t)(int)__builtin_amdgcn_fmed3f(rintf(u), 0.0f, levels);
+}
+
+// One thread = 16 consecutive channels of one token; a group of G channels = G/16 neighbouring threads.
+// Returns the thread's 16 codes; the group's first thread stores scale and zero-point at meta_at.
+template <int BITS, int G>
+__device__ inline void pt_quantize_slice(const uint16_t *row16, uint16_t *sc, uint16_t *zp, int slice, uint32_t (&codes)[16])
+{
+    constexpr float levels = (float)((1 << BITS) - 1);
+    const uint4 a = reinterpret_cast<const uint4 *>(row16)[0], b = reinterpret_cast<const uint4 *>(row16)[1];
+    const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    float x[16];
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        x[2 * i] = pt_h2f((uint16_t)(w[i] & 0xffffu));
+        x[2 * i + 1] = pt_h2f((uint16_t)(w[i] >> 16));
+    }
+    float mn = x[0], mx = x[0];
+#pragma unroll
+    for (int i = 1; i < 16; i++) { mn = fminf(mn, x[i]); mx = fmaxf(mx, x[i]); }
+#pragma unroll
+    for (int d = 1; d < G / 16; d <<= 1) {           // the G/16 threads of the group are neighbours in the wave
+        mn = fminf(mn, __shfl_xor(mn, d));
+        mx = fmaxf(mx, __shfl_xor(mx, d));
+    }
+    uint16_t sh, zh;
+    float inv, zf;
+    pt_group_params(mn, mx, levels, sh, zh, inv, zf);
+    if ((slice & (G / 16 - 1)) == 0) { sc[slice / (G / 16)] = sh; zp[slice / (G / 16)] = zh; }
+#pragma unroll
+    for (int i = 0; i < 16; i++) codes[i] = pt_code(x[i], zf, inv, levels);
+}
+
+template <int BITS, int G>
+__global__ __launch_bounds__(256) void quantize_pack_pt_kernel(PtQuantArgs a)
+{
+    constexpr int CPW = 32 / BITS, NG = kD / G;
+    __shared__ uint8_t vcode[kPtBlockTok][kD + 4];     // V codes of the block, one byte each (row pitch 132)
+
+    const int u = blockIdx.y, tid = threadIdx.x;
+    int q0;
+    const int n = pt_tokens_to_append(a, u, q0);
+    const int i0 = blockIdx.x * kPtBlockTok;
+    if (i0 >= n) return;
+    const int nt = min(kPtBlockTok, n - i0);           // multiple of 16
+    const int t0 = q0 + i0;
+
+    const int slice = tid & 7;                         // 16-channel slice of the token
+    for (int i = tid >> 3; i < nt; i += 32) {
+        long row = a.idx ? (long)a.idx[(size_t)u * a.idx_stride + i0 + i] : (long)(i0 + i);
+        row = row < 0 ? 0 : (row >= a.L ? a.L - 1 : row);
+        const size_t src = ((size_t)u * a.L + row) * kD + slice * 16;
+        const size_t meta = ((size_t)u * a.Tcap + (size_t)(t0 + i)) * NG;
+        uint32_t codes[16];
+        // keys: the codes of a token are contiguous, 16 codes = 16 * BITS / 32 words
+        pt_quantize_slice<BITS, G>(a.K + src, a.Ks + meta, a.Kz + meta, slice, codes);
+        uint32_t *kdst = a.Kc + ((size_t)u * a.Tcap + (size_t)(t0 + i)) * (kD / CPW) + slice * (16 / CPW);
+#pragma unroll
+        for (int wv = 0; wv < 16 / CPW; wv++) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int j = 0; j < CPW; j++) word |= codes[wv * CPW + j] << (BITS * j);
+            kdst[wv] = word;
+        }
+        // values: codes go through LDS, the words run along the tokens
+        pt_quantize_slice<BITS, G>(a.V + src, a.Vs + meta, a.Vz + meta, slice, codes);
+#pragma unroll
+        for (int j = 0; j < 16; j++) vcode[i][slice * 16 + j] = (uint8_t)codes[j];
+    }
+    __syncthreads();
+    uint32_t *vdst = a.Vc + (size_t)u * (size_t)(a.Tcap / CPW) * kD + (size_t)(t0 / CPW) * kD;
+    for (int wi = tid; wi < (nt / CPW) * kD; wi += 256) {
+        const int r = wi / kD, c = wi % kD;
+        uint32_t word = 0;
+#pragma unroll
+        for (int j = 0; j < CPW; j++) word |= (uint32_t)vcode[r * CPW + j][c] << (BITS * j);
+        vdst[(size_t)r * kD + c] = word;
+    }
+}
+
+__global__ void update_lengths_pt_kernel(PtQuantArgs a, int units)
+{
+    const int u = blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= units) return;
+    int q0;
+    const int n = pt_tokens_to_append(a, u, q0);
+    if (n) a.q_len[u] = q0 + n;
+}
+
+// ------------------------------------------------------------------------------------------------ decode
+struct PtDecArgs {
+    const uint16_t *q;
+    const uint32_t *Kc, *Vc;
+    const uint16_t *Ks, *Kz, *Vs, *Vz;
+    const int32_t *q_len;
+    uint16_t *out;
+    float *ws;                    // partials [B*Hq][nchunk][kPartialStride]: m, l, 2 pad, o[128]
+    float c1;                     // sm_scale * log2(e)
+    int Hq, Hkv, rep, Tcap, chunk, nchunk;
+};
+
+__device__ inline float pt_wave_max(float v)
+{
+    for (int o = 32; o; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ inline float pt_wave_sum(float v)
+{
+    for (int o = 32; o; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// One workgroup = one (unit, chunk of tokens), all query heads of the unit.  Per inner block of 256 tokens:
+// score phase, one token per thread -- sum_c q_c * (code * Ks + Kz) = sum_g Ks_g * (sum_{c in g} q_c code_c)
+// + Kz_g * (sum_{c in g} q_c), so the codes meet the query before any scale does --; block-wide online
+// softmax; value phase, one channel per thread, the weights times the token's V scale read from LDS, the
+// zero-point term kept per token thread and reduced once at the end.
+template <int BITS, int G>
+__global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
+{
+    constexpr int CPW = 32 / BITS, NG = kD / G, W = kD / CPW;
+    constexpr uint32_t MASK = (1u << BITS) - 1u;
+    __shared__ __attribute__((aligned(16))) float qs[kPtMaxRep][kD];          // q * sm_scale * log2(e)
+    __shared__ float qsum[kPtMaxRep][NG];                                     // its sums over the channel groups
+    __shared__ __attribute__((aligned(16))) float wgt[kPtMaxRep][NG][kPtSB];  // weight * V scale of the block's tokens
+    __shared__ float red[4][kPtMaxRep];
+    __shared__ float comb[kPtMaxRep][kD];
+    __shared__ float zsum[kPtMaxRep][NG];
+
+    const int u = blockIdx.y, ch = blockIdx.x, tid = threadIdx.x, rep = a.rep;
+    const int b = u / a.Hkv, kvh = u % a.Hkv;
+    const int bq0 = b * a.Hq + kvh * rep;
+    const int T = min(max(a.q_len[u], 0), a.Tcap);
+    const int t_begin = ch * a.chunk, t_end = min(T, t_begin + a.chunk);
+    if (t_begin >= t_end) return;                       // the merge kernel skips this slot
+
+    for (int i = tid; i < rep * kD; i += 256)
+        qs[i / kD][i % kD] = pt_h2f(a.q[(size_t)(bq0 + i / kD) * kD + i % kD]) * a.c1;
+    __syncthreads();
+    if (tid < rep * NG) {
+        const int h = tid / NG, g = tid % NG;
+        float s = 0.f;
+        for (int c = 0; c < G; c++) s += qs[h][g * G + c];
+        qsum[h][g] = s;
+    }
+    __syncthreads();
+
+    const uint32_t *Kc = a.Kc + (size_t)u * a.Tcap * W;
+    const uint32_t *Vc = a.Vc + (size_t)u * (size_t)(a.Tcap / CPW) * kD;
+    const uint16_t *Ks = a.Ks + (size_t)u * a.Tcap * NG, *Kz = a.Kz + (size_t)u * a.Tcap * NG;
+    const uint16_t *Vs = a.Vs + (size_t)u * a.Tcap * NG, *Vz = a.Vz + (size_t)u * a.Tcap * NG;
+
+    float m[kPtMaxRep], l[kPtMaxRep], o[kPtMaxRep], pz[kPtMaxRep][NG];
+#pragma unroll
+    for (int h = 0; h < kPtMaxRep; h++) {
+        m[h] = -1e30f; l[h] = 0.f; o[h] = 0.f;
+#pragma unroll
+        for (int g = 0; g < NG; g++) pz[h][g] = 0.f;
+    }
+    const int c = tid & (kD - 1), half = tid >> 7, cg = c / G;
+
+    for (int ts = t_begin; ts < t_end; ts += kPtSB) {
+        // ---- scores of token ts + tid
+        const int t = ts + tid;
+        const bool valid = t < t_end;
+        const int tc = valid ? t : t_end - 1;
+        float s[kPtMaxRep];
+#pragma unroll
+        for (int h = 0; h < kPtMaxRep; h++) s[h] = 0.f;
+        {
+            const uint4 *kw4 = reinterpret_cast<const uint4 *>(Kc + (size_t)tc * W);
+            float dot[NG][kPtMaxRep];
+#pragma unroll
+            for (int g = 0; g < NG; g++)
+#pragma unroll
+                for (int h = 0; h < kPtMaxRep; h++) dot[g][h] = 0.f;
+#pragma unroll
+            for (int w4 = 0; w4 < W / 4; w4++) {
+                const uint4 q4 = kw4[w4];
+                const uint32_t ww[4] = {q4.x, q4.y, q4.z, q4.w};
+#pragma unroll
+                for (int wi = 0; wi < 4; wi++) {
+                    const int c0 = (w4 * 4 + wi) * CPW;          // first channel of this word
+                    const int g = c0 / G;                        // (a word never straddles two groups: CPW <= 16 < G)
+#pragma unroll
+                    for (int j = 0; j < CPW; j += 4) {
+                        const int cc = c0 + j;
+                        const float k0 = (float)((ww[wi] >> (BITS * j)) & MASK);
+                        const float k1 = (float)((ww[wi] >> (BITS * (j + 1))) & MASK);
+                        const float k2 = (float)((ww[wi] >> (BITS * (j + 2))) & MASK);
+                        const float k3 = (float)((ww[wi] >> (BITS * (j + 3))) & MASK);
+#pragma unroll
+                        for (int h = 0; h < kPtMaxRep; h++) {
+                            if (h < rep) {
+                                const float4 qq = *reinterpret_cast<const float4 *>(&qs[h][cc]);
+                                dot[g][h] += qq.x * k0 + qq.y * k1 + qq.z * k2 + qq.w * k3;
+                            }
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < NG; g++) {
+                const float ks = pt_h2f(Ks[(size_t)tc * NG + g]), kz = pt_h2f(Kz[(size_t)tc * NG + g]);
+#pragma unroll
+                for (int h = 0; h < kPtMaxRep; h++)
+                    if (h < rep) s[h] += ks * dot[g][h] + kz * qsum[h][g];
+            }
+        }
+        // ---- block max, weights, block sum
+#pragma unroll
+        for (int h = 0; h < kPtMaxRep; h++) {
+            if (h < rep) {
+                s[h] = valid ? s[h] : -INFINITY;
+                const float wm = pt_wave_max(s[h]);
+                if ((tid & 63) == 0) red[tid >> 6][h] = wm;
+            }
+        }
+        __syncthreads();
+        float scale[kPtMaxRep], p[kPtMaxRep];
+#pragma unroll
+        for (int h = 0; h < kPtMaxRep; h++) {
+            if (h < rep) {
+                const float bm = fmaxf(fmaxf(red[0][h], red[1][h]), fmaxf(red[2][h], red[3][h]));
+                const float mn = fmaxf(m[h], bm);
+                scale[h] = exp2f(m[h] - mn);
+                m[h] = mn;
+                p[h] = exp2f(s[h] - mn);                // exp2(-inf) = 0 for the masked tail
+            }
+        }
+        __syncthreads();
+        {
+            float vs[NG], vz[NG];
+#pragma unroll
+            for (int g = 0; g < NG; g++) { vs[g] = pt_h2f(Vs[(size_t)tc * NG + g]); vz[g] = pt_h2f(Vz[(size_t)tc * NG + g]); }
+#pragma unroll
+            for (int h = 0; h < kPtMaxRep; h++) {
+                if (h < rep) {
+                    const float ws = pt_wave_sum(p[h]);
+                    if ((tid & 63) == 0) red[tid >> 6][h] = ws;
+#pragma unroll
+                    for (int g = 0; g < NG; g++) {
+                        wgt[h][g][tid] = p[h] * vs[g];
+                        pz[h][g] = pz[h][g] * scale[h] + p[h] * vz[g];
+                    }
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int h = 0; h < kPtMaxRep; h++) {
+            if (h < rep) {
+                l[h] = l[h] * scale[h] + (red[0][h] + red[1][h] + red[2][h] + red[3][h]);
+                o[h] *= scale[h];
+            }
+        }
+        // ---- weighted values: thread (c, half) takes tokens [half*128, half*128 + 128) of the block
+        const int nb = min(kPtSB, t_end - ts);          // multiple of 16
+        for (int tt = half * 128; tt < min(nb, half * 128 + 128); tt += CPW) {
+            const uint32_t word = Vc[(size_t)((ts + tt) / CPW) * kD + c];
+#pragma unroll
+            for (int j = 0; j < CPW; j += 4) {
+                const float v0 = (float)((word >> (BITS * j)) & MASK), v1 = (float)((word >> (BITS * (j + 1))) & MASK);
+                const float v2 = (float)((word >> (BITS * (j + 2))) & MASK), v3 = (float)((word >> (BITS * (j + 3))) & MASK);
+#pragma unroll
+                for (int h = 0; h < kPtMaxRep; h++) {
+                    if (h < rep) {
+                        const float4 w4 = *reinterpret_cast<const float4 *>(&wgt[h][cg][tt + j]);
+                        o[h] += w4.x * v0 + w4.y * v1 + w4.z * v2 + w4.w * v3;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- zero-point term: sum over the token threads, per (head, channel group)
+    if (tid < kPtMaxRep * NG) zsum[tid / NG][tid % NG] = 0.f;
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < kPtMaxRep; h++) {
+        if (h < rep) {
+#pragma unroll
+            for (int g = 0; g < NG; g++) {
+                const float wsum = pt_wave_sum(pz[h][g]);
+                if ((tid & 63) == 0) atomicAdd(&zsum[h][g], wsum);
+            }
+        }
+    }
+    if (half == 1)
+        for (int h = 0; h < rep; h++) comb[h][c] = o[h];
+    __syncthreads();
+    if (half == 0)
+        for (int h = 0; h < rep; h++) {
+            float *pp = a.ws + ((size_t)(bq0 + h) * a.nchunk + ch) * kPartialStride;
+            pp[4 + c] = o[h] + comb[h][c] + zsum[h][cg];
+            if (c == 0) { pp[0] = m[h]; pp[1] = l[h]; }
+        }
+}
+
+// One workgroup of 128 threads per query row: combine the partials of the chunks that hold tokens.
+__global__ __launch_bounds__(128) void merge_pt_kernel(PtDecArgs a)
+{
+    const int bq = blockIdx.x, c = threadIdx.x;
+    const int u = (bq / a.Hq) * a.Hkv + (bq % a.Hq) / a.rep;
+    const int T = min(max(a.q_len[u], 0), a.Tcap);
+    const int nq = (T + a.chunk - 1) / a.chunk;
+    const float *base = a.ws + (size_t)bq * a.nchunk * kPartialStride;
+    float M = -1e30f;
+    for (int ch = 0; ch < nq; ch++) M = fmaxf(M, base[(size_t)ch * kPartialStride]);
+    float L = 0.f, O = 0.f;
+    for (int ch = 0; ch < nq; ch++) {
+        const float *p = base + (size_t)ch * kPartialStride;
+        const float w = exp2f(p[0] - M);
+        L += p[1] * w;
+        O += p[4 + c] * w;
+    }
+    a.out[(size_t)bq * kD + c] = __half_as_ushort(__float2half_rn(L > 0.f ? O / L : 0.f));
+}
+
+static int pt_validate_shape(const minikv_pt_shape *s)
+{
+    if (!s) return MINIKV_EINVAL;
+    if (s->D != kD) return MINIKV_EUNSUPPORTED;
+    if (!(s->G == 32 || s->G == 64 || s->G == 128)) return MINIKV_EUNSUPPORTED;
+    if (!(s->bits == 2 || s->bits == 4 || s->bits == 8)) return MINIKV_EUNSUPPORTED;
+    if (s->B <= 0 || s->Hq <= 0 || s->Hkv <= 0 || s->Hq % s->Hkv) return MINIKV_EINVAL;
+    if (s->Hq / s->Hkv > kPtMaxRep) return MINIKV_EUNSUPPORTED;
+    if (s->Tcap <= 0 || s->Tcap % 64) return MINIKV_EINVAL;
+    if ((int64_t)s->B * s->Hkv > 65535) return MINIKV_EINVAL;
+    return MINIKV_OK;
+}
+
+static int pt_validate_cache(const minikv_pt_cache *c)
+{
+    if (!c) return MINIKV_EINVAL;
+    if (!aligned16(c->Kc) || !aligned16(c->Ks) || !aligned16(c->Kz) || !aligned16(c->Vc) || !aligned16(c->Vs) ||
+        !aligned16(c->Vz) || !c->q_len)
+        return MINIKV_EINVAL;
+    return MINIKV_OK;
+}
+
+// token chunk of one decode workgroup: enough workgroups to cover the chip a few times over
+static int pt_chunk(const minikv_pt_shape &s)
+{
+    const long units = (long)s.B * s.Hkv;
+    int chunk = kPtSB;
+    while (chunk < 8192 && units * ((s.Tcap + 2 * chunk - 1) / (2 * chunk)) >= 1024) chunk *= 2;
+    return chunk;
+}
+
+template <int BITS>
+static int pt_launch_quantize(const PtQuantArgs &a, int G, dim3 grid, int units, hipStream_t st)
+{
+    switch (G) {
+    case 32: hipLaunchKernelGGL((quantize_pack_pt_kernel<BITS, 32>), grid, dim3(256), 0, st, a); break;
+    case 64: hipLaunchKernelGGL((quantize_pack_pt_kernel<BITS, 64>), grid, dim3(256), 0, st, a); break;
+    case 128: hipLaunchKernelGGL((quantize_pack_pt_kernel<BITS, 128>), grid, dim3(256), 0, st, a); break;
+    default: return MINIKV_EUNSUPPORTED;
+    }
+    hipLaunchKernelGGL(update_lengths_pt_kernel, dim3((units + 255) / 256), dim3(256), 0, st, a, units);
+    return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
+}
+
+template <int BITS>
+static int pt_launch_decode(const PtDecArgs &a, int G, dim3 grid, hipStream_t st)
+{
+    switch (G) {
+    case 32: hipLaunchKernelGGL((decode_pt_kernel<BITS, 32>), grid, dim3(256), 0, st, a); break;
+    case 64: hipLaunchKernelGGL((decode_pt_kernel<BITS, 64>), grid, dim3(256), 0, st, a); break;
+    case 128: hipLaunchKernelGGL((decode_pt_kernel<BITS, 128>), grid, dim3(256), 0, st, a); break;
+    default: return MINIKV_EUNSUPPORTED;
+    }
+    return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
+}
+
+}  // namespace minikv
+
+using namespace minikv;
+
+extern "C" {
+
+size_t minikv_pt_cache_bytes(const minikv_pt_shape *s, int which)
+{
+    if (pt_validate_shape(s) != MINIKV_OK) return 0;
+    const size_t U = (size_t)s->B * s->Hkv;
+    switch (which) {
+    case MINIKV_BUF_KC:
+    case MINIKV_BUF_VC: return U * (size_t)s->Tcap * (size_t)(kD * s->bits / 8);
+    case MINIKV_BUF_KS:
+    case MINIKV_BUF_KZ:
+    case MINIKV_BUF_VS:
+    case MINIKV_BUF_VZ: return U * (size_t)s->Tcap * (size_t)(kD / s->G) * 2;
+    case MINIKV_BUF_QLEN: return U * 4;
+    default: return 0;
+    }
+}
+
+size_t minikv_pt_workspace_bytes(const minikv_pt_shape *s)
+{
+    if (pt_validate_shape(s) != MINIKV_OK) return 0;
+    const int chunk = pt_chunk(*s);
+    const size_t nchunk = (size_t)(s->Tcap + chunk - 1) / chunk;
+    return (size_t)s->B * s->Hq * nchunk * kPartialStride * sizeof(float);
+}
+
+int kv_quantize_pack_pt(const minikv_pt_shape *s, const minikv_f16 *K, const minikv_f16 *V, int64_t L,
+                        const int32_t *idx, int64_t idx_stride, const int32_t *n_tok, int32_t max_tok,
+                        minikv_pt_cache *c, void *stream)
+{
+    int rc = pt_validate_shape(s);
+    if (rc) return rc;
+    if ((rc = pt_validate_cache(c))) return rc;
+    if (!aligned16(K) || !aligned16(V) || !n_tok || L <= 0) return MINIKV_EINVAL;
+    if (max_tok < 0 || max_tok % 16 || max_tok > s->Tcap || max_tok > L) return MINIKV_EINVAL;
+    if (idx && idx_stride < max_tok) return MINIKV_EINVAL;
+    if (max_tok == 0) return MINIKV_OK;
+    PtQuantArgs a;
+    a.K = K; a.V = V; a.idx = idx; a.n_tok = n_tok;
+    a.Kc = c->Kc; a.Vc = c->Vc; a.Ks = c->Ks; a.Kz = c->Kz; a.Vs = c->Vs; a.Vz = c->Vz; a.q_len = c->q_len;
+    a.L = L; a.idx_stride = idx_stride; a.Tcap = s->Tcap; a.max_tok = max_tok;
+    const int units = s->B * s->Hkv;
+    const dim3 grid((max_tok + kPtBlockTok - 1) / kPtBlockTok, units);
+    switch (s->bits) {
+    case 2: return pt_launch_quantize<2>(a, s->G, grid, units, (hipStream_t)stream);
+    case 4: return pt_launch_quantize<4>(a, s->G, grid, units, (hipStream_t)stream);
+    case 8: return pt_launch_quantize<8>(a, s->G, grid, units, (hipStream_t)stream);
+    }
+    return MINIKV_EUNSUPPORTED;
+}
+
+int minikv_decode_attn_pt(const minikv_pt_shape *s, const minikv_f16 *q, const minikv_pt_cache *c, float sm_scale,
+                          minikv_f16 *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = pt_validate_shape(s);
+    if (rc) return rc;
+    if ((rc = pt_validate_cache(c))) return rc;
+    if (!aligned16(q) || !aligned16(out) || !aligned16(workspace)) return MINIKV_EINVAL;
+    if (!(sm_scale == sm_scale) || sm_scale - sm_scale != 0.0f) return MINIKV_EINVAL;
+    if (workspace_bytes < minikv_pt_workspace_bytes(s)) return MINIKV_EWORKSPACE;
+    PtDecArgs a;
+    a.q = q; a.Kc = c->Kc; a.Vc = c->Vc; a.Ks = c->Ks; a.Kz = c->Kz; a.Vs = c->Vs; a.Vz = c->Vz; a.q_len = c->q_len;
+    a.out = out;
+    a.ws = reinterpret_cast<float *>(workspace);
+    a.c1 = sm_scale * 1.44269504088896340736f;
+    a.Hq = s->Hq; a.Hkv = s->Hkv; a.rep = s->Hq / s->Hkv; a.Tcap = s->Tcap;
+    a.chunk = pt_chunk(*s);
+    a.nchunk = (s->Tcap + a.chunk - 1) / a.chunk;
+    const dim3 grid(a.nchunk, s->B * s->Hkv);
+    switch (s->bits) {
+    case 2: rc = pt_launch_decode<2>(a, s->G, grid, (hipStream_t)stream); break;
+    case 4: rc = pt_launch_decode<4>(a, s->G, grid, (hipStream_t)stream); break;
+    case 8: rc = pt_launch_decode<8>(a, s->G, grid, (hipStream_t)stream); break;
+    default: return MINIKV_EUNSUPPORTED;
+    }
+    if (rc) return rc;
+    hipLaunchKernelGGL(merge_pt_kernel, dim3(s->B * s->Hq), dim3(128), 0, (hipStream_t)stream, a);
+    return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
+}
+
+}  // extern "C"

@@ -155,3 +155,31 @@ def test_static_workspace_entry_point_refuses_what_does_not_fit(api):
     assert l.minikv_decode_attn_static(C.byref(bad), P(0x1000), C.byref(cache), C.c_float(1.0), P(0x1000), None) == -2
     assert l.minikv_decode_attn_static(C.byref(api.make_shape(1, 4, 1, 128, 32, 256, 32)), None, C.byref(cache),
                                        C.c_float(1.0), P(0x1000), None) == -1
+
+
+def test_per_token_variant_sizes_and_host_checks(api):
+    """minikv_pt_cache_bytes follows the documented layout (the appendix's 4-bit case: 68 bytes per token, head and
+    tensor against 256 in fp16) and the entry points refuse bad arguments before anything is launched."""
+    l, P = api.lib(), C.c_void_p
+    s = api.make_pt_shape(2, 8, 2, 128, 128, 4, 256)
+    U = 4
+    sizes = [int(l.minikv_pt_cache_bytes(C.byref(s), i)) for i in range(10)]
+    assert sizes[:7] == [U * 256 * 64, U * 256 * 2, U * 256 * 2, U * 256 * 64, U * 256 * 2, U * 256 * 2, U * 4]
+    assert sizes[7:] == [0, 0, 0]
+    assert (sizes[0] + sizes[1] + sizes[2]) == U * 256 * 68 and round(256 / 68, 2) == 3.76
+    assert int(l.minikv_pt_workspace_bytes(C.byref(s))) >= 2 * 8 * 132 * 4
+    cache = api.MinikvPtCache(*([0x1000] * 7))
+    good = (P(0x1000), P(0x1000), 64, None, 0, P(0x1000))
+    for bad, status in ((dict(bits=3), -2), (dict(G=16), -2), (dict(Tcap=100), -1), (dict(Hq=7), -1), (dict(Hq=32, Hkv=2), -2),
+                        (dict(D=64), -2)):
+        kw = dict(B=2, Hq=8, Hkv=2, D=128, G=128, bits=4, Tcap=256); kw.update(bad)
+        sb = api.make_pt_shape(**kw)
+        assert l.kv_quantize_pack_pt(C.byref(sb), *good, 64, C.byref(cache), None) == status
+        assert int(l.minikv_pt_cache_bytes(C.byref(sb), 0)) == 0
+    assert l.kv_quantize_pack_pt(C.byref(s), *good, 24, C.byref(cache), None) == -1          # bound not a multiple of 16
+    assert l.kv_quantize_pack_pt(C.byref(s), *good, 128, C.byref(cache), None) == -1         # bound beyond L
+    assert l.kv_quantize_pack_pt(C.byref(s), *good, 0, C.byref(cache), None) == 0            # nothing to do
+    assert l.kv_quantize_pack_pt(C.byref(s), None, P(0x1000), 64, None, 0, P(0x1000), 64, C.byref(cache), None) == -1
+    assert l.minikv_decode_attn_pt(C.byref(s), P(0x1000), C.byref(cache), 1.0, P(0x1000), P(0x1000), 16, None) == -3
+    assert l.minikv_decode_attn_pt(C.byref(s), P(0x1000), C.byref(cache), float("inf"), P(0x1000), P(0x1000), 1 << 30, None) == -1
+    assert l.minikv_decode_attn_pt(C.byref(s), P(0x1004), C.byref(cache), 1.0, P(0x1000), P(0x1000), 1 << 30, None) == -1

@@ -1,0 +1,149 @@
+"""GPU parity of the per-token quantized variant (kv_quantize_pack_pt, minikv_decode_attn_pt) against its
+oracle: packed buffers bit for bit, attention output to 2e-3; and, on the GPU paths themselves, the ordering of
+errors on keys with outlier channels that the paper's appendix on token-wise quantization reports (2-bit
+per-token keys fail, 4 and 8 bits and 2-bit per-channel keys hold)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2411_18077_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+PT_RAW = ("Kc", "Ks", "Kz", "Vc", "Vs", "Vz", "q_len")
+
+
+def _inputs(B, Hq, Hkv, L, seed, keep=0.5, ragged=False, n_outlier=3):
+    w = W.Workload("pt", B=B, Hq=Hq, Hkv=Hkv, L=L, keep=None if ragged else keep, G=16, Rcap=0, seed=seed,
+                   n_outlier=n_outlier, outlier_scale=8.0, keep_range=(0.05, 1.0) if ragged else None)
+    return w, W.make_inputs(w, "cuda")            # retained counts are multiples of 16 (the workload's G)
+
+
+def _both_caches(api, ref, w, inp, G, bits, Tcap=None):
+    Tcap = Tcap or max(64, (int(inp.n_tok.max()) + 63) // 64 * 64)
+    s = api.make_pt_shape(w.B, w.Hq, w.Hkv, 128, G, bits, Tcap)
+    gc = api.PtCache(s)
+    api.kv_quantize_pack_pt(s, inp.K, inp.V, w.L, inp.idx, inp.idx.shape[1], inp.n_tok, int(inp.n_tok.max()), gc)
+    torch.cuda.synchronize()
+    rs = ref.RefPtShape(w.B, w.Hq, w.Hkv, 128, G, bits, Tcap)
+    rc = ref.RefPtCache(rs)
+    assert ref.quantize_pack_pt(rc, inp.K.cpu().numpy(), inp.V.cpu().numpy(), inp.n_tok.cpu().numpy(), inp.idx.cpu().numpy()) == 0
+    return s, gc, rc
+
+
+def _assert_bit_exact(gc, rc):
+    U = rc.q_len.shape[0]
+    for name in PT_RAW:
+        g = gc.t[name].cpu().numpy()
+        r = getattr(rc, name)
+        g = np.ascontiguousarray(g[: r.size].reshape(U, -1)).view(np.uint8)
+        rb = np.ascontiguousarray(r.reshape(U, -1)).view(np.uint8)
+        if not np.array_equal(g, rb):
+            bad = np.argwhere(g != rb)
+            raise AssertionError("%s differs at %d bytes, first (unit, byte) = %s" % (name, len(bad), bad[0]))
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("G", [32, 64, 128])
+def test_quantize_bit_exact_and_decode_within_tolerance(bits, G):
+    from oracle import ref
+    from paper_2411_18077_amd import api
+    w, inp = _inputs(2, 8, 2, 1536, seed=500 + bits + G, ragged=True)
+    s, gc, rc = _both_caches(api, ref, w, inp, G, bits)
+    _assert_bit_exact(gc, rc)
+    out = torch.full((w.B, w.Hq, 128), float("nan"), dtype=torch.float16, device="cuda")
+    sm = 1.0 / math.sqrt(128)
+    api.minikv_decode_attn_pt(s, inp.q, gc, sm, out)
+    torch.cuda.synchronize()
+    want, _ = ref.decode_attn_pt(rc, inp.q.cpu().numpy(), sm)
+    got = out.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    assert np.max(np.abs(got - want.astype(np.float32))) <= TOL
+
+
+@pytest.mark.parametrize("Hq,Hkv,B", [(4, 4, 2), (12, 3, 1), (8, 1, 2), (5, 5, 1), (14, 2, 1)])
+def test_head_counts_empty_units_and_many_chunks(Hq, Hkv, B):
+    """Every Hq/Hkv up to 8 that the host check accepts in some case here (1, 4, 8, 7), a unit without tokens,
+    and a context long enough for several token chunks per unit."""
+    from oracle import ref
+    from paper_2411_18077_amd import api
+    w, inp = _inputs(B, Hq, Hkv, 6144, seed=520 + Hq, keep=0.75)
+    inp.n_tok[0] = 0
+    inp.n_tok[-1] = 16
+    s, gc, rc = _both_caches(api, ref, w, inp, 64, 4)
+    _assert_bit_exact(gc, rc)
+    out = torch.full((w.B, w.Hq, 128), float("nan"), dtype=torch.float16, device="cuda")
+    sm = 1.0 / math.sqrt(128)
+    api.minikv_decode_attn_pt(s, inp.q, gc, sm, out)
+    torch.cuda.synchronize()
+    want, _ = ref.decode_attn_pt(rc, inp.q.cpu().numpy(), sm)
+    got = out.float().cpu().numpy()
+    assert np.max(np.abs(got - want.astype(np.float32))) <= TOL
+    assert not got.reshape(B * Hkv, Hq // Hkv, 128)[0].any()          # unit 0 holds nothing -> zeros
+
+
+def test_appending_twice_and_refused_units():
+    from oracle import ref
+    from paper_2411_18077_amd import api
+    w, inp = _inputs(1, 4, 4, 512, seed=540, keep=1.0)
+    Tcap = 512
+    s = api.make_pt_shape(1, 4, 4, 128, 32, 4, Tcap)
+    gc = api.PtCache(s)
+    rs = ref.RefPtShape(1, 4, 4, 128, 32, 4, Tcap)
+    rc = ref.RefPtCache(rs)
+    K, V = inp.K.cpu().numpy(), inp.V.cpu().numpy()
+    first = torch.tensor([128, 64, 16, 256], dtype=torch.int32, device="cuda")
+    api.kv_quantize_pack_pt(s, inp.K, inp.V, 512, None, 0, first, 256, gc)
+    assert ref.quantize_pack_pt(rc, K, V, first.cpu().numpy()) == 0
+    # second call: rows 256.. of the same tensors; unit 1 asks for a count that is not a multiple of 16, unit 3
+    # for more than the bound the host passes: both stay as they are
+    second = torch.tensor([64, 40, 32, 192], dtype=torch.int32, device="cuda")
+    api.kv_quantize_pack_pt(s, inp.K[:, 256:].contiguous(), inp.V[:, 256:].contiguous(), 256, None, 0, second, 128, gc)
+    torch.cuda.synchronize()
+    second_ref = second.cpu().numpy().copy(); second_ref[1] = 0; second_ref[3] = 0
+    assert ref.quantize_pack_pt(rc, np.ascontiguousarray(K[:, 256:]), np.ascontiguousarray(V[:, 256:]), second_ref) == 0
+    assert gc.q_len.cpu().tolist() == [192, 64, 48, 256]
+    _assert_bit_exact(gc, rc)
+
+
+def test_outlier_channels_break_two_bit_per_token_keys_on_the_gpu_paths():
+    """Keys with a few large-magnitude channels: through kv_quantize_pack_pt + minikv_decode_attn_pt with 2, 4
+    and 8 bits and through the 2-bit per-channel path (kv_quantize_pack + minikv_decode_attn), against
+    attention on the unquantized fp16 tensors (numpy, fp64)."""
+    from scipy.special import softmax
+    from paper_2411_18077_amd import api
+    B, Hq, Hkv, L = 1, 4, 4, 512
+    gen = torch.Generator(device="cuda"); gen.manual_seed(81)
+    K = torch.randn(Hkv, L, 128, generator=gen, device="cuda")
+    K[:, :, [3, 40, 77, 101]] *= 12.0
+    K = K.to(torch.float16)
+    V = torch.randn(Hkv, L, 128, generator=gen, device="cuda").to(torch.float16)
+    q = torch.randn(B, Hq, 128, generator=gen, device="cuda")
+    q[:, :, [3, 40, 77, 101]] *= 0.2
+    q = q.to(torch.float16)
+    sm = 0.088
+    n_tok = torch.full((Hkv,), L, dtype=torch.int32, device="cuda")
+    Kd, Vd, qd = (x.double().cpu().numpy() for x in (K, V, q))
+    exact = np.stack([softmax(float(np.float32(sm)) * (Kd[h] @ qd[0, h])) @ Vd[h] for h in range(Hq)])
+    err = {}
+    for bits in (2, 4, 8):
+        s = api.make_pt_shape(B, Hq, Hkv, 128, 128, bits, L)
+        c = api.PtCache(s)
+        api.kv_quantize_pack_pt(s, K, V, L, None, 0, n_tok, L, c)
+        out = torch.zeros(B, Hq, 128, dtype=torch.float16, device="cuda")
+        api.minikv_decode_attn_pt(s, q, c, sm, out)
+        torch.cuda.synchronize()
+        err["pt%d" % bits] = float(np.abs(out[0].double().cpu().numpy() - exact).max())
+    s = api.make_shape(B, Hq, Hkv, 128, 32, L, 0)
+    c = api.Cache(s)
+    api.kv_quantize_pack(s, K, V, L, None, 0, n_tok, L, c)
+    out = torch.zeros(B, Hq, 128, dtype=torch.float16, device="cuda")
+    api.minikv_decode_attn(s, q, c, sm, out)
+    torch.cuda.synchronize()
+    err["per_channel2"] = float(np.abs(out[0].double().cpu().numpy() - exact).max())
+    print(err)
+    assert err["pt8"] < err["pt4"] < err["pt2"]
+    assert err["per_channel2"] < 0.5 * err["pt2"]
+    assert err["pt2"] > 4 * err["pt4"]
