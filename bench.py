@@ -5,14 +5,15 @@ One "step" = kv_append_residual (the new token's K/V row) + minikv_decode_attn o
 cache, i.e. the per-token hot path of Algorithm 1's Decoding procedure.  Every step runs on its OWN
 seeded cache copy (different data, different addresses), so nothing is served from L2 or the Infinity
 Cache and no state has to be reset inside the timed region; all inputs are resident in HBM before the
-clock starts.  The prefill-side kv_quantize_pack and the flush are timed separately and reported in
-extra fields of the same JSON line.
+clock starts.  The other four baseline configurations, the prefill-side kv_quantize_pack, the flush, the
+token selection, the prefill attention and the per-token quantized variant are timed separately and
+reported in extra fields of the same JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4] [--variant V]
 
 Prints ONE JSON line (see the keys below).  `value` is effective HBM GB/s = algorithmic bytes per step
 / time per step; `roofline` is the decode kernel against the 8 TB/s HBM peak; `cpu_baseline` is the CPU
-oracle timed on a bounded sample of the same workload.
+oracle timed on the same workload.
 """
 import argparse
 import json
@@ -51,6 +52,105 @@ def parse():
     return ap.parse_args()
 
 
+def build_copies(api, W, torch, w, ncopy, dev, keep_first_inputs=False):
+    """ncopy seeded cache copies of workload w, prefill-quantized on the GPU, residual one short of full.
+    Returns (shape, copies, first inputs or None, kv_quantize_pack times in ms, bytes the quantizer moved)."""
+    shape = None
+    copies, quant_ms = [], []
+    first = None
+    gathered_bytes = 0
+    for i in range(ncopy):
+        inp = W.make_inputs(w, dev, seed_offset=i)
+        if shape is None:
+            # ragged workloads draw new lengths for every copy: size the caches for the longest possible
+            tcap = w.tcap(w.L // w.G * w.G) if w.keep_range is not None else inp.Tcap
+            shape = api.make_shape(w.B, w.Hq, w.Hkv, w.D, w.G, tcap, w.Rcap)
+        cache = api.Cache(shape, device=dev)
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        api.kv_quantize_pack(shape, inp.K, inp.V, w.L, inp.idx, inp.idx.shape[1], inp.n_tok, int(inp.n_tok.max()), cache)
+        e1.record()
+        r0 = w.Rcap - 1                                    # the timed step appends the last residual token
+        cache.Rk.view(w.units, w.Rcap, w.D)[:, :r0].copy_(inp.Rk[:, :r0])
+        cache.Rv.view(w.units, w.Rcap, w.D)[:, :r0].copy_(inp.Rv[:, :r0])
+        cache.r_len.fill_(r0)
+        k_new = inp.Rk[:, r0].contiguous()
+        v_new = inp.Rv[:, r0].contiguous()
+        out = torch.zeros(w.B, w.Hq, w.D, dtype=torch.float16, device=dev)
+        torch.cuda.synchronize()
+        quant_ms.append(e0.elapsed_time(e1))
+        copies.append(dict(cache=cache, q=inp.q, k_new=k_new, v_new=v_new, out=out, n_tok=inp.n_tok))
+        if i == 0:
+            nt = int(inp.n_tok.sum())
+            gathered_bytes = nt * w.D * 2 * 2 + nt * (64 + 8 * w.D // w.G)
+            if keep_first_inputs:
+                first = inp
+        del inp
+        if i == 1 and (ncopy - 2) * (cache.nbytes() + 64 * 2**20) > torch.cuda.mem_get_info()[0] * 0.8:
+            ncopy = max(2, int(torch.cuda.mem_get_info()[0] * 0.8 / (cache.nbytes() + 64 * 2**20)))
+        if len(copies) >= ncopy:
+            break
+    return shape, copies, first, quant_ms, gathered_bytes
+
+
+def time_attention(api, torch, shape, copies, sm, steps, offset=0):
+    """Average duration of back-to-back minikv_decode_attn launches (one event pair around all of them: the
+    figure holds the kernel and the dispatch of the next one) and the median of singly bracketed launches."""
+    n = len(copies)
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(steps):
+        c = copies[(offset + i) % n]
+        api.minikv_decode_attn(shape, c["q"], c["cache"], sm, c["out"])
+    e1.record()
+    torch.cuda.synchronize()
+    avg_ms = e0.elapsed_time(e1) / steps
+    evs = []
+    for i in range(steps):
+        c = copies[(offset + i) % n]
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        api.minikv_decode_attn(shape, c["q"], c["cache"], sm, c["out"])
+        b.record()
+        evs.append((a, b))
+    torch.cuda.synchronize()
+    durs = sorted(a.elapsed_time(b) for a, b in evs)
+    return avg_ms, durs[len(durs) // 2]
+
+
+def parity_sample(api, W, torch, np, ref, w, shape, inp, got_out, units, sm):
+    """Oracle on the listed units of the inputs `inp` (cache rebuilt by the oracle from the same rows) against the
+    GPU output got_out [B, Hq, D] of the step that appended the last residual token.  Returns (parity dict,
+    seconds of the oracle's quantizer, seconds per decode run, bytes of the sampled units)."""
+    rep = w.Hq // w.Hkv
+    dev = inp.K.device
+    sel = torch.as_tensor(units, device=dev)
+    rs = ref.RefShape(len(units), rep, 1, w.D, w.G, int(shape.Tcap), w.Rcap)
+    rc = ref.RefCache(rs)
+    t0 = time.perf_counter()
+    assert ref.quantize_pack(rc, inp.K[sel].cpu().numpy(), inp.V[sel].cpu().numpy(),
+                             inp.n_tok[sel].cpu().numpy(), inp.idx[sel].cpu().numpy()) == 0
+    t_quant = time.perf_counter() - t0
+    rc.Rk[:] = inp.Rk[sel].cpu().numpy(); rc.Rv[:] = inp.Rv[sel].cpu().numpy(); rc.r_len[:] = w.Rcap
+    qs = inp.q.view(w.B, w.Hkv, rep, w.D).reshape(w.units, rep, w.D)[sel].cpu().numpy()
+    times = []
+    for _ in range(3):
+        a = time.perf_counter()
+        want, _, _ = ref.decode_attn(rc, qs, sm)
+        times.append(time.perf_counter() - a)
+    got = got_out.view(w.B, w.Hkv, rep, w.D).reshape(w.units, rep, w.D)[sel].float().cpu().numpy()
+    # tolerance: 2e-3, or one fp16 step of the oracle's value where that is larger (|o| >= 2)
+    wantf = want.astype(np.float32)
+    diff = np.abs(got - wantf)
+    step16 = np.spacing(np.abs(want).astype(np.float16)).astype(np.float32)
+    q_len = inp.n_tok.cpu().tolist()
+    par = {"max_abs_err_vs_oracle": float(diff.max()), "tolerance": "max(2e-3, one fp16 step of the value)",
+           "max_abs_oracle_value": float(np.abs(wantf).max()), "sample_units": len(units),
+           "ok": bool(np.all(diff <= np.maximum(2e-3, step16)))}
+    return par, t_quant, sorted(times)[1], W.algorithmic_bytes(w, [q_len[u] for u in units], [w.Rcap] * len(units))
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -77,49 +177,14 @@ def main():
     ncopy = args.steps + args.warmup
     if args.max_copies:
         ncopy = min(ncopy, args.max_copies)
-    free_b, _ = torch.cuda.mem_get_info()
-    copies = []
-    shape = None
-    sample_src = None
     t_build = time.time()
-    quant_times = []
-    for i in range(ncopy):
-        inp = W.make_inputs(w, dev, seed_offset=i)
-        if shape is None:
-            # ragged workloads draw new lengths for every copy: size the caches for the longest possible
-            tcap = w.tcap(w.L // w.G * w.G) if w.keep_range is not None else inp.Tcap
-            shape = api.make_shape(w.B, w.Hq, w.Hkv, w.D, w.G, tcap, w.Rcap)
-        cache = api.Cache(shape, device=dev)
-        n_max = int(inp.n_tok.max())
-        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        api.kv_quantize_pack(shape, inp.K, inp.V, w.L, inp.idx, inp.idx.shape[1], inp.n_tok, n_max, cache)
-        e1.record()
-        # residual holds Rcap-1 tokens; the timed step appends the last one
-        r0 = w.Rcap - 1
-        cache.Rk.view(w.units, w.Rcap, w.D)[:, :r0].copy_(inp.Rk[:, :r0])
-        cache.Rv.view(w.units, w.Rcap, w.D)[:, :r0].copy_(inp.Rv[:, :r0])
-        cache.r_len.fill_(r0)
-        k_new = inp.Rk[:, r0].contiguous()
-        v_new = inp.Rv[:, r0].contiguous()
-        out = torch.zeros(w.B, w.Hq, w.D, dtype=torch.float16, device=dev)
-        torch.cuda.synchronize()
-        quant_times.append(e0.elapsed_time(e1))
-        copies.append(dict(cache=cache, q=inp.q, k_new=k_new, v_new=v_new, out=out, n_tok=inp.n_tok))
-        if i == 0:
-            sample_src = inp                               # kept for the parity / cpu-baseline sample
-            gathered_bytes = int(inp.n_tok.sum()) * w.D * 2 * 2 + int(inp.n_tok.sum()) * (64 + 8 * w.D // w.G)
-        else:
-            del inp
-        if i == 1 and (ncopy - 2) * (cache.nbytes() + 64 * 2**20) > torch.cuda.mem_get_info()[0] * 0.8:
-            ncopy = max(2, int(torch.cuda.mem_get_info()[0] * 0.8 / (cache.nbytes() + 64 * 2**20)))
+    shape, copies, sample_src, quant_times, gathered_bytes = build_copies(api, W, torch, w, ncopy, dev, keep_first_inputs=True)
     ncopy = len(copies)
     t_build = time.time() - t_build
 
     q_len = copies[0]["n_tok"].cpu().tolist()
     bytes_of = [W.algorithmic_bytes(w, c["n_tok"].cpu().tolist(), [w.Rcap] * w.units) for c in copies]
     alg_bytes = int(round(sum(bytes_of[(args.warmup + i) % ncopy] for i in range(args.steps)) / args.steps))
-    append_bytes = 2 * w.units * w.D * 2 * 2               # read + write of the new K and V rows
 
     def step(i):
         c = copies[i % ncopy]
@@ -147,29 +212,7 @@ def main():
     value = alg_bytes / (ms_per_step * 1e-3) / 1e9
 
     # ------------------------------------------------------------------ timing of the attention launch alone (events)
-    # One pair of events around K back-to-back launches (each on its own cache copy): the average then
-    # holds the kernel and the dispatch of the next one, not the cost of recording events in between.
-    # A second loop brackets every launch with its own pair, for the spread.
-    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for i in range(args.steps):
-        c = copies[(args.warmup + i) % ncopy]
-        api.minikv_decode_attn(shape, c["q"], c["cache"], sm, c["out"])
-    e1.record()
-    torch.cuda.synchronize()
-    attn_ms_avg = e0.elapsed_time(e1) / args.steps
-    evs = []
-    for i in range(args.steps):
-        c = copies[(args.warmup + i) % ncopy]
-        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
-        a.record()
-        api.minikv_decode_attn(shape, c["q"], c["cache"], sm, c["out"])
-        b.record()
-        evs.append((a, b))
-    torch.cuda.synchronize()
-    durs = sorted(a.elapsed_time(b) for a, b in evs)
-    attn_ms_med = durs[len(durs) // 2]
+    attn_ms_avg, attn_ms_med = time_attention(api, torch, shape, copies, sm, args.steps, offset=args.warmup)
     achieved = alg_bytes / (attn_ms_avg * 1e-3) / 1e9
 
     result = {
@@ -182,7 +225,6 @@ def main():
         "ms_per_step": round(ms_per_step, 5),
         "us_per_step": round(ms_per_step * 1e3, 2),
         "higher_is_better": True,
-        "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f16",
         "data": "synthetic",
@@ -204,53 +246,33 @@ def main():
         },
     }
 
-    # ------------------------------------------------------------------ parity + CPU baseline on a bounded sample
+    # ------------------------------------------------------------------ parity + CPU baseline: the oracle on the whole workload
     if not args.no_cpu_baseline:
         from oracle import ref
-        import numpy as np
-        nsamp = min(w.units, 64)
-        rng = np.random.default_rng(w.seed)
-        units = sorted(rng.choice(w.units, nsamp, replace=False).tolist())
-        if w.keep is None:                                 # ragged: make sure the extremes are in
-            units = sorted(set(units[:-2] + [int(np.argmin(q_len)), int(np.argmax(q_len))]))
-            nsamp = len(units)
-        rep = w.Hq // w.Hkv
-        inp = sample_src
-        sel = torch.as_tensor(units, device=dev)
-        rs = ref.RefShape(nsamp, rep, 1, w.D, w.G, int(shape.Tcap), w.Rcap)
-        rc = ref.RefCache(rs)
-        t_q0 = time.perf_counter()
-        assert ref.quantize_pack(rc, inp.K[sel].cpu().numpy(), inp.V[sel].cpu().numpy(),
-                                 inp.n_tok[sel].cpu().numpy(), inp.idx[sel].cpu().numpy()) == 0
-        t_q1 = time.perf_counter()
-        rc.Rk[:] = inp.Rk[sel].cpu().numpy(); rc.Rv[:] = inp.Rv[sel].cpu().numpy(); rc.r_len[:] = w.Rcap
-        qs = inp.q.view(w.B, w.Hkv, rep, w.D).reshape(w.units, rep, w.D)[sel].cpu().numpy()
-        times = []
-        for _ in range(5):
-            a = time.perf_counter()
-            want, _, _ = ref.decode_attn(rc, qs, sm)
-            times.append(time.perf_counter() - a)
-        cpu_s = sorted(times)[2]
-        samp_bytes = W.algorithmic_bytes(w, [q_len[u] for u in units], [w.Rcap] * nsamp)
-        got = copies[0]["out"].view(w.B, w.Hkv, rep, w.D).reshape(w.units, rep, w.D)[sel].float().cpu().numpy()
-        # copies[0] was last run in the event loop or the timed loop; its output is the step's result
-        # tolerance: 2e-3, or one fp16 step of the oracle's value where that is larger (|o| >= 2)
-        wantf = want.astype(np.float32)
-        diff = np.abs(got - wantf)
-        step16 = np.spacing(np.abs(want).astype(np.float16)).astype(np.float32)
-        err = float(diff.max())
-        result["parity"] = {"max_abs_err_vs_oracle": err, "tolerance": "max(2e-3, one fp16 step of the value)",
-                            "max_abs_oracle_value": float(np.abs(wantf).max()), "sample_units": nsamp,
-                            "ok": bool(np.all(diff <= np.maximum(2e-3, step16)))}
+        # every unit while that stays within about 10-30 s of CPU work, else a seeded sample (the extremes of a
+        # ragged workload included)
+        total_tok = sum(q_len)
+        if total_tok * (w.Hq // w.Hkv) <= 8_000_000:
+            units = list(range(w.units))
+        else:
+            rng = np.random.default_rng(w.seed)
+            units = sorted(rng.choice(w.units, min(w.units, 32), replace=False).tolist())
+            if w.keep is None:
+                units = sorted(set(units[:-2] + [int(np.argmin(q_len)), int(np.argmax(q_len))]))
+        # copies[0] was last run by the attention timing loops: its output is the step's result
+        par, t_quant, cpu_s, samp_bytes = parity_sample(api, W, torch, np, ref, w, shape, sample_src, copies[0]["out"], units, sm)
+        result["parity"] = par
         result["cpu_baseline"] = {
             "value": round(samp_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())),
             "kind": "oracle",
-            "sample": "%d of %d (batch, KV-head) units of %s, all query heads, median of 5 runs (%.2f s each)"
-                      % (nsamp, w.units, w.name, cpu_s),
-            "quantize_pack_s": round(t_q1 - t_q0, 3),
+            "sample": "%d of %d (batch, KV-head) units of %s, all query heads, median of 3 runs (%.2f s each)"
+                      % (len(units), w.units, w.name, cpu_s),
+            "quantize_pack_s": round(t_quant, 3),
         }
+    del sample_src
 
     if not args.no_extras:
+        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
         qt = sorted(quant_times[1:] or quant_times)
         q_ms = qt[len(qt) // 2]
         result["quantize_pack"] = {
@@ -259,13 +281,23 @@ def main():
         }
         # flush: every unit quantizes its full residual (n_r tokens) into the packed cache
         c = copies[0]
-        a = torch.cuda.Event(enable_timing=True); b = torch.cuda.Event(enable_timing=True)
         a.record()
         api.kv_flush_residual(shape, c["cache"])
         b.record()
         torch.cuda.synchronize()
         result["flush_residual"] = {"ms": round(a.elapsed_time(b), 4), "tokens_per_unit": w.Rcap,
                                     "amortised_us_per_step": round(a.elapsed_time(b) * 1e3 / w.Rcap, 3)}
+        # the allocation-free entry point on the same copies (same kernel, workspace inside the library)
+        if api.lib().minikv_static_workspace_units() >= w.units * ((w.Hq // w.Hkv + 3) // 4):
+            for i in range(4 + args.steps):
+                if i == 4:
+                    a.record()
+                cc = copies[i % ncopy]
+                api.minikv_decode_attn_static(shape, cc["q"], cc["cache"], sm, cc["out"])
+            b.record()
+            torch.cuda.synchronize()
+            result["decode_attn_static"] = {"what": "minikv_decode_attn_static, back-to-back launches",
+                                            "us": round(a.elapsed_time(b) * 1e3 / args.steps, 2)}
         # reference point: a plain streaming read of 4 GiB (far beyond the 256 MB Infinity Cache), best of 5
         probe_src = torch.empty(1 << 30, dtype=torch.int32, device=dev).fill_(1)
         probe_sums = torch.zeros(2048, dtype=torch.int32, device=dev)
@@ -309,7 +341,10 @@ def main():
             "what": "kv_select_hh_rw on this shape (sum of the group's query heads, top n_hh by score + recent "
                     "window, ascending positions), mean of %d back-to-back calls" % reps,
             "us": round(sel_us, 2), "bytes": sel_bytes, "GB/s": round(sel_bytes / sel_us / 1e3, 1),
+            "frac_of_hbm_peak": round(sel_bytes / sel_us / 1e3 / HBM_PEAK_GBS, 3),
         }
+        del A, sel_idx, sel_ws
+
         # prefill attention with cumulative scores (both passes), one sequence with this workload's heads and
         # context, and the longest prompt of the paper's kernel table (8192 tokens, 32 heads)
         def time_prefill(Bp, Hq, Hkv, Lp, reps):
@@ -341,7 +376,100 @@ def main():
                 "paper_ms_a100": [5.21, 14.85, 48.04, 187.83],
             },
         }
-        result["build_s"] = round(t_build, 1)
+
+        # per-token quantized variant (the appendix's 4-bit baseline: bits = 4, one group per head) on this shape
+        inp = W.make_inputs(w, dev, seed_offset=0)
+        n16 = (inp.n_tok // 16 * 16).to(torch.int32)
+        tcap_pt = (int(n16.max()) + 63) // 64 * 64
+        pts = api.make_pt_shape(w.B, w.Hq, w.Hkv, w.D, 128, 4, tcap_pt)
+        ptc = [api.PtCache(pts) for _ in range(3)]
+        pt_q_ms = []
+        for pc in ptc:
+            a.record()
+            api.kv_quantize_pack_pt(pts, inp.K, inp.V, w.L, inp.idx, inp.idx.shape[1], n16, int(n16.max()), pc)
+            b.record()
+            torch.cuda.synchronize()
+            pt_q_ms.append(a.elapsed_time(b))
+        pt_out = torch.zeros(w.B, w.Hq, w.D, dtype=torch.float16, device=dev)
+        reps = 12
+        for i in range(3 + reps):
+            if i == 3:
+                a.record()
+            api.minikv_decode_attn_pt(pts, inp.q, ptc[i % 3], sm, pt_out)
+        b.record()
+        torch.cuda.synchronize()
+        pt_us = a.elapsed_time(b) * 1e3 / reps
+        pt_bytes = int(n16.sum()) * 2 * (w.D * 4 // 8 + 4) + 2 * w.B * w.Hq * w.D * 2
+        pt_qbytes = int(n16.sum()) * (w.D * 2 * 2 + 2 * (w.D * 4 // 8 + 4))
+        result["per_token_4bit_variant"] = {
+            "what": "kv_quantize_pack_pt / minikv_decode_attn_pt with bits = 4, G = 128 (keys and values per token, the "
+                    "appendix's 4-bit baseline) on this shape; 3 cache copies in rotation",
+            "decode_us": round(pt_us, 2), "decode_bytes": pt_bytes, "decode_GB/s": round(pt_bytes / pt_us / 1e3, 1),
+            "decode_frac_of_hbm_peak": round(pt_bytes / pt_us / 1e3 / HBM_PEAK_GBS, 3),
+            "quantize_ms": round(sorted(pt_q_ms)[1], 4), "quantize_GB/s": round(pt_qbytes / (sorted(pt_q_ms)[1] * 1e-3) / 1e9, 1),
+        }
+        del inp, ptc
+
+        # ---------------------------------------------------------------- the other baseline configurations
+        del copies
+        torch.cuda.empty_cache()
+        others = {}
+        for ow in W.WORKLOADS:
+            if ow.name == w.name:
+                continue
+            cache_mb = W.algorithmic_bytes(ow, [int(ow.L * (ow.keep or 0.55))] * ow.units, [ow.Rcap] * ow.units) / 1e6
+            nc = int(min(12, max(3, math.ceil(600.0 / max(cache_mb, 1.0)))))        # > 512 MB of distinct caches in rotation
+            oshape, ocopies, oinp, oq_ms, _ = build_copies(api, W, torch, ow, nc, dev, keep_first_inputs=True)
+            osteps = 40
+            for i in range(len(ocopies)):                                            # the step: append, then attend
+                oc = ocopies[i]
+                api.kv_append_residual(oshape, oc["k_new"], oc["v_new"], oc["cache"])
+                api.minikv_decode_attn(oshape, oc["q"], oc["cache"], sm, oc["out"])
+            torch.cuda.synchronize()
+            o_avg, o_med = time_attention(api, torch, oshape, ocopies, sm, osteps)
+            ob = [W.algorithmic_bytes(ow, oc["n_tok"].cpu().tolist(), [ow.Rcap] * ow.units) for oc in ocopies]
+            o_bytes = int(round(sum(ob[i % len(ocopies)] for i in range(osteps)) / osteps))
+            entry = {"us_per_launch": round(o_avg * 1e3, 2), "median_single_launch_us": round(o_med * 1e3, 2),
+                     "algorithmic_bytes": o_bytes, "GB/s": round(o_bytes / (o_avg * 1e-3) / 1e9, 1),
+                     "frac_of_hbm_peak": round(o_bytes / (o_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "cache_copies": len(ocopies)}
+            if not args.no_cpu_baseline:
+                from oracle import ref
+                oq = ocopies[0]["n_tok"].cpu().tolist()
+                rng = np.random.default_rng(ow.seed)
+                ou = sorted(rng.choice(ow.units, min(ow.units, 4), replace=False).tolist())
+                if ow.keep is None:
+                    ou = sorted(set(ou[:-2] + [int(np.argmin(oq)), int(np.argmax(oq))]))
+                par, _, o_cpu_s, o_sb = parity_sample(api, W, torch, np, ref, ow, oshape, oinp, ocopies[0]["out"], ou, sm)
+                entry["parity"] = par
+                entry["oracle_GB/s"] = round(o_sb / o_cpu_s / 1e9, 4)
+            if ow.name.startswith("cfg3"):
+                # the prefill of this configuration: kv_quantize_pack of ALL 16384 tokens of every unit (no gather)
+                inp3 = oinp
+                full_n = torch.full((ow.units,), ow.L, dtype=torch.int32, device=dev)
+                s3 = api.make_shape(ow.B, ow.Hq, ow.Hkv, ow.D, ow.G, ow.L, ow.Rcap)
+                c3 = api.Cache(s3, device=dev)
+                t3 = []
+                for _ in range(3):
+                    c3.q_len.zero_()
+                    a.record()
+                    api.kv_quantize_pack(s3, inp3.K, inp3.V, ow.L, None, 0, full_n, ow.L, c3)
+                    b.record()
+                    torch.cuda.synchronize()
+                    t3.append(a.elapsed_time(b))
+                b3 = ow.units * ow.L * (ow.D * 2 * 2 + 64 + 8 * ow.D // ow.G)
+                entry["prefill_quantize_pack_all_tokens"] = {
+                    "tokens_per_unit": ow.L, "ms": round(sorted(t3)[1], 4), "bytes": b3,
+                    "GB/s": round(b3 / (sorted(t3)[1] * 1e-3) / 1e9, 1),
+                    "frac_of_hbm_peak": round(b3 / (sorted(t3)[1] * 1e-3) / 1e9 / HBM_PEAK_GBS, 3)}
+                del c3, inp3
+            others[ow.name] = entry
+            del ocopies, oinp
+            torch.cuda.empty_cache()
+        result["other_configurations"] = {
+            "what": "minikv_decode_attn on the other baseline configurations (back-to-back launches over rotating cache "
+                    "copies, parity of one step against the oracle on sampled units)", **others}
+        result["input_build_s"] = round(t_build, 1)
 
     print(json.dumps(result))
 

@@ -17,6 +17,11 @@ extern "C" {
  * xor-updated with a checksum per workgroup. */
 int minikv_stream_read_probe(const void *src, size_t bytes, uint32_t *sums, void *stream);
 
+/* How many (wave, unit) pairs minikv_decode_attn has redone with range-normalised operands since `workspace` was
+ * zero-filled (the second attempt taken when an fp16 matrix operand overflowed, see minikv.h): 0 for data inside
+ * the fast range.  Synchronous (a blocking 4-byte copy to the host); count is a HOST pointer. */
+int minikv_diag_redo_count(const minikv_shape *shape, const void *workspace, int32_t *count);
+
 /* Selects the kernel minikv_decode_attn launches (process-wide):
  *   0 = default, 1 = a plain scalar-loop fp32 kernel (two launches) kept as a second GPU implementation of
  *   Algorithm 1 lines 17-19 for cross-checks, 3 = the default kernel by its own number.

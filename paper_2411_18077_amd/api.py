@@ -97,6 +97,8 @@ def lib():
                                            C.c_size_t, P]
         l.selective_flash_attn_workspace_bytes.restype = C.c_size_t
         l.selective_flash_attn_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int64]
+        l.minikv_diag_redo_count.restype = C.c_int
+        l.minikv_diag_redo_count.argtypes = [C.POINTER(MinikvShape), P, C.POINTER(C.c_int32)]
         l.minikv_stream_read_probe.restype = C.c_int
         l.minikv_stream_read_probe.argtypes = [P, C.c_size_t, P, P]
         l.kv_select_workspace_bytes.restype = C.c_size_t
@@ -227,6 +229,12 @@ def kv_pyramid_budget(n_layers, x, d, bottom_heavy):
 def minikv_stream_read_probe(src, sums, stream=None):
     _check(lib().minikv_stream_read_probe(_ptr(src), src.numel() * src.element_size(), _ptr(sums), _stream(stream)),
            "minikv_stream_read_probe")
+
+
+def minikv_diag_redo_count(shape, workspace):
+    n = C.c_int32(0)
+    _check(lib().minikv_diag_redo_count(C.byref(shape), _ptr(workspace), C.byref(n)), "minikv_diag_redo_count")
+    return int(n.value)
 
 
 def minikv_set_variant(v):

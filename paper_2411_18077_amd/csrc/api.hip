@@ -231,6 +231,13 @@ int minikv_stream_read_probe(const void *src, size_t bytes, uint32_t *sums, void
     return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
 }
 
+int minikv_diag_redo_count(const minikv_shape *s, const void *workspace, int32_t *count)
+{
+    if (validate_shape(s) != MINIKV_OK || !workspace || !count) return MINIKV_EINVAL;
+    const int *p = reinterpret_cast<const int *>(workspace) + 3 * ws_units(*s) + kMaxStreamWaves;
+    return hipMemcpy(count, p, sizeof(int32_t), hipMemcpyDeviceToHost) == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
+}
+
 int minikv_set_variant(int variant)
 {
     if (!(variant == 0 || variant == 1 || variant == 3)) return MINIKV_EINVAL;

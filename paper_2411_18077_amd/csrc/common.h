@@ -18,14 +18,16 @@ constexpr int kMaxStreamWaves = 4096;  // most single-wave workgroups the decode
 
 // Workspace layout of the single-launch decode kernel: ticket counters (zero between calls) -- one per
 // (unit, set of 4 query heads) and one per partial slot for the sub-groups of 16 waves -- then the split-K
-// partials (slot = wave + 2 * unit, fewer than kMaxStreamWaves + 2 * units of them).
+// partials (slot = wave + 2 * unit, fewer than kMaxStreamWaves + 2 * units of them).  One more word behind the
+// ticket counters counts the units that had to be redone with range-normalised operands (never reset by the
+// kernels; read by minikv_diag_redo_count).
 __host__ __device__ inline size_t ws_units(const minikv_shape &s)
 {
     return (size_t)s.B * s.Hkv * ((s.Hq / s.Hkv + 3) / 4);
 }
 __host__ __device__ inline size_t ws_counter_bytes(const minikv_shape &s)
 {
-    return ((3 * ws_units(s) + kMaxStreamWaves) * sizeof(int) + 255) / 256 * 256;
+    return ((3 * ws_units(s) + kMaxStreamWaves + 1) * sizeof(int) + 255) / 256 * 256;
 }
 
 // per-unit element counts
@@ -78,9 +80,9 @@ int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache
                   minikv_f16 *out, void *workspace, int variant, hipStream_t st);
 
 // the same with the three parts of the workspace given one by one: per-unit ticket counters (ws_units ints),
-// sub-group ticket counters (2 * ws_units + kMaxStreamWaves ints), split-K partials
+// sub-group ticket counters (2 * ws_units + kMaxStreamWaves ints), the redo counter (one int), split-K partials
 int launch_decode_parts(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
-                        minikv_f16 *out, int *cnt, int *cnt1, float *partials, int variant, hipStream_t st);
+                        minikv_f16 *out, int *cnt, int *cnt1, int *redo, float *partials, int variant, hipStream_t st);
 int validate_cache(const minikv_shape &s, const minikv_cache *c);
 bool aligned16(const void *p);
 

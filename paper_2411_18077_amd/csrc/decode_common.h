@@ -14,6 +14,7 @@ struct DecArgs {
     float *ws;                   // split-K partials (layout depends on the variant)
     int *cnt;                    // per-unit ticket counters of the single-launch kernel (zero between calls)
     int *cnt1;                   // ticket counters of the sub-groups, indexed by the sub-group's first slot
+    int *redo;                   // counts (wave, unit) pairs redone with range-normalised operands (diagnostics)
     int first_slot;              // workgroups that fill the first wave slot of every SIMD
     int skew16;                  // sixteenths of a wave pair's range that its first wave takes
     float c1;                    // sm_scale * log2(e): scores are kept in the base-2 domain

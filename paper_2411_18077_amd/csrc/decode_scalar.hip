@@ -192,13 +192,13 @@ int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache
                   minikv_f16 *out, void *workspace, int variant, hipStream_t st)
 {
     int *cnt = reinterpret_cast<int *>(workspace);
-    return launch_decode_parts(s, q, c, sm_scale, out, cnt, cnt + ws_units(s),
+    return launch_decode_parts(s, q, c, sm_scale, out, cnt, cnt + ws_units(s), cnt + 3 * ws_units(s) + kMaxStreamWaves,
                                reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + ws_counter_bytes(s)),
                                variant, st);
 }
 
 int launch_decode_parts(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
-                        minikv_f16 *out, int *cnt, int *cnt1, float *partials, int variant, hipStream_t st)
+                        minikv_f16 *out, int *cnt, int *cnt1, int *redo, float *partials, int variant, hipStream_t st)
 {
     const DecodeGeom g = decode_geom(s);
     DecArgs a;
@@ -208,6 +208,7 @@ int launch_decode_parts(const minikv_shape &s, const minikv_f16 *q, const minikv
     a.first_slot = 0;
     a.cnt = cnt;
     a.cnt1 = cnt1;
+    a.redo = redo;
     a.ws = partials;
     a.c1 = sm_scale * 1.44269504088896340736f;
     a.Hq = s.Hq; a.Hkv = s.Hkv; a.rep = g.rep; a.Tcap = s.Tcap; a.Rcap = s.Rcap;

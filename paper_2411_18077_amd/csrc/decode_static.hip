@@ -14,7 +14,7 @@ constexpr size_t kStaticUnits = 2048;
 // used to zero), then the split-K partial slots (no initial state).
 constexpr size_t kStaticCnt = kStaticUnits;                                   // per-unit counters
 constexpr size_t kStaticCnt1 = 2 * kStaticUnits + kMaxStreamWaves;            // sub-group counters
-constexpr size_t kStaticCounterBytes = ((kStaticCnt + kStaticCnt1) * sizeof(int) + 255) / 256 * 256;
+constexpr size_t kStaticCounterBytes = ((kStaticCnt + kStaticCnt1 + 1) * sizeof(int) + 255) / 256 * 256;   // + the redo counter
 constexpr size_t kStaticPartialBytes = ((size_t)kMaxStreamWaves + 2 * kStaticUnits) * 4 * kPartialStride * sizeof(float);
 constexpr size_t kStaticBytes = kStaticCounterBytes + kStaticPartialBytes;    // about 17.3 MB per GPU
 
@@ -71,7 +71,7 @@ int minikv_decode_attn_static(const minikv_shape *s, const minikv_f16 *q, const 
     unsigned char *base = scratch_of_current_device((hipStream_t)stream);
     if (!base) return MINIKV_ELAUNCH;
     int *cnt = reinterpret_cast<int *>(base);
-    return launch_decode_parts(*s, q, *c, sm_scale, out, cnt, cnt + kStaticCnt,
+    return launch_decode_parts(*s, q, *c, sm_scale, out, cnt, cnt + kStaticCnt, cnt + kStaticCnt + kStaticCnt1,
                                reinterpret_cast<float *>(base + kStaticCounterBytes), 0, (hipStream_t)stream);
 }
 

@@ -341,6 +341,7 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
 #pragma nounroll
         for (int attempt = 0; attempt < 2; attempt++) {
         const bool safe = attempt != 0;
+        if (safe && lane == 0) atomicAdd(a.redo, 1);       // (diagnostics: how often the second attempt is taken)
         const float hd = safe ? -1.0f : 4.0f;
         const float lg = hd - (float)fld_shift(lane & 7);
         const float vun = safe ? 33554432.0f : 1048576.0f; // 2^24 (subnormal fields) / 2^hd (ps headroom)
@@ -742,10 +743,11 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             }
         }
         {
-            // any overflowed operand has left an infinity or a NaN in one of the sums
+            // any overflowed operand has left an infinity or a NaN in one of the sums (of the heads in use:
+            // with paired rows the accumulators of rows 2 and 3 hold nothing meaningful)
             float chk = 0.f;
 #pragma unroll
-            for (int h = 0; h < kNH; h++) chk += (O0[h] + O1[h]) + l_lane[h];
+            for (int h = 0; h < NHQ; h++) chk += (O0[h] + O1[h]) + l_lane[h];
             if (__ballot(!(chk - chk == 0.f)) == 0) break;
         }
         }   // attempt

@@ -25,7 +25,7 @@ def test_exports_every_declared_symbol(api):
     names = sorted(set(names))
     assert {"kv_quantize_pack", "kv_append_residual", "kv_flush_residual", "minikv_decode_attn",
             "minikv_workspace_bytes", "minikv_buffer_bytes", "minikv_cache_bytes", "minikv_abi_version", "kv_select_hh_rw",
-            "minikv_set_variant", "minikv_stream_read_probe",
+            "minikv_set_variant", "minikv_stream_read_probe", "minikv_diag_redo_count",
             "kv_select_workspace_bytes", "kv_pyramid_budget", "selective_flash_attn",
             "selective_flash_attn_workspace_bytes"} <= set(names)
     l = api.lib()

@@ -45,6 +45,7 @@ def run_both(g, w, r_len, variant, Tcap=None, seed_offset=0, mutate=None, sm=Non
     want, _, _ = ref.decode_attn(rc, g.to_np(inp.q), sm)
     got = g.to_np(out).astype(np.float64)
     assert np.isfinite(got).all()
+    run_both.redone = api.minikv_diag_redo_count(s, gc.workspace)       # units the kernel had to do twice
     return got, want.astype(np.float64)
 
 
@@ -66,6 +67,7 @@ def test_decode_matches_oracle(g, variant, G, Hq, Hkv):
     w = tiny(G, Hq=Hq, Hkv=Hkv)
     got, want = run_both(g, w, r_len=w.Rcap, variant=variant)
     assert np.max(np.abs(got - want)) <= TOL
+    assert run_both.redone == 0          # ordinary data never takes the second, range-normalised attempt
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
@@ -126,6 +128,7 @@ def test_head_counts_not_a_power_of_two(g, variant, G, Hq, Hkv, B, r_full):
     w = tiny(G, B=B, Hq=Hq, Hkv=Hkv, L=1024, keep=None, keep_range=(0.1, 1.0), Rcap=max(G, 64), seed=300 + Hq)
     got, want = run_both(g, w, r_len=w.Rcap if r_full else 0, variant=variant)
     assert np.max(np.abs(got - want)) <= TOL
+    assert run_both.redone == 0
 
 
 # ---------------------------------------------------------------------------------------------------------
@@ -156,6 +159,8 @@ def test_value_scales_up_to_the_fp16_range(g, variant, vmax, peaked):
 
     got, want = run_both(g, w, r_len=w.Rcap, variant=variant, mutate=mutate)
     _assert_close_in_fp16_steps(got, want, vscale=vmax / 3.0)
+    if variant != 1:                     # inside the range: one attempt; far beyond it: the second one is taken
+        assert (run_both.redone == 0) == (vmax == 6000.0)
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
@@ -182,6 +187,9 @@ def test_query_times_key_scale_up_to_the_fp16_range(g, variant, target, peaked):
     got, want = run_both(g, w, r_len=w.Rcap, variant=variant, prepare=prepare, sm=sm)
     assert 0.9 * target <= seen["max"] <= 1.01 * target
     _assert_close_in_fp16_steps(got, want)
+    if variant != 1 and target == 6.0e4:
+        assert run_both.redone == 0      # (beyond 65504 the first attempt overflows only where the product meets
+                                         #  a channel whose code field carries no down-scaling, so no claim there)
 
 
 @pytest.mark.parametrize("variant", VARIANTS)

@@ -40,6 +40,7 @@ def test_full_config_sampled_units(g, name):
     api.minikv_decode_attn(shape, inp.q, cache, 1.0 / math.sqrt(w.D), out)
     torch.cuda.synchronize()
     assert torch.isfinite(out).all()
+    assert api.minikv_diag_redo_count(shape, cache.workspace) == 0      # no unit needed the second attempt
 
     n_tok = inp.n_tok.cpu().numpy()
     if w.units <= 256:
