@@ -540,3 +540,47 @@ int selective_flash_attn_ref(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, int3
     }
     return failed ? -1 : 0;
 }
+
+/* The same attention for a list of query rows of ONE head (eq. (1), causal): what a full-size check can afford.
+ * rows[r] in [0, L).  xo [n_rows][D], lse [n_rows]; p_tail [n_rows][tail] receives the row's weights of the LAST
+ * `tail` keys (P[row][L - tail + t], zero for keys after the row), from which the caller can add up the
+ * cumulative score of a late column over all the rows that see it.  Any output may be NULL. */
+int selective_flash_attn_rows_ref(int64_t L, int32_t D, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
+                                  float sm_scale, const int64_t *rows, int32_t n_rows, double *xo, double *lse,
+                                  double *p_tail, int32_t tail)
+{
+    if (L < 1 || D < 1 || !Q || !K || !V || !rows || n_rows < 0 || tail < 0 || tail > L) return -1;
+    for (int r = 0; r < n_rows; ++r)
+        if (rows[r] < 0 || rows[r] >= L) return -1;
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int r = 0; r < n_rows; ++r) {
+        const int64_t i = rows[r];
+        double *p = (double *)malloc(sizeof(double) * (size_t)(i + 1));
+        if (!p) { failed = 1; continue; }
+        double m = -INFINITY, sum = 0.0;
+        for (int64_t j = 0; j <= i; ++j) {
+            double s = 0.0;
+            for (int c = 0; c < D; ++c)
+                s += (double)ref_f16_to_f32(Q[i * D + c]) * (double)ref_f16_to_f32(K[j * D + c]);
+            p[j] = s * (double)sm_scale;
+            if (p[j] > m) m = p[j];
+        }
+        for (int64_t j = 0; j <= i; ++j) { p[j] = exp(p[j] - m); sum += p[j]; }
+        for (int64_t j = 0; j <= i; ++j) p[j] /= sum;
+        if (lse) lse[r] = m + log(sum);
+        if (xo)
+            for (int c = 0; c < D; ++c) {
+                double o = 0.0;
+                for (int64_t j = 0; j <= i; ++j) o += p[j] * (double)ref_f16_to_f32(V[j * D + c]);
+                xo[(size_t)r * (size_t)D + (size_t)c] = o;
+            }
+        if (p_tail)
+            for (int t = 0; t < tail; ++t) {
+                const int64_t j = L - tail + t;
+                p_tail[(size_t)r * (size_t)tail + (size_t)t] = j <= i ? p[j] : 0.0;
+            }
+        free(p);
+    }
+    return failed ? -1 : 0;
+}

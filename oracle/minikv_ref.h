@@ -100,6 +100,13 @@ int selective_flash_attn_ref(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, int3
                              const uint16_t *K, const uint16_t *V, float sm_scale, uint16_t *XO_f16,
                              double *XO_f64, double *lse, double *A_cumul);
 
+/* The same quantities for a list of query rows of ONE head (Q, K, V [L][D] of that head), for checks at sizes
+ * where the whole matrix is out of reach: xo [n_rows][D] (fp64), lse [n_rows], and p_tail [n_rows][tail] = the
+ * row's weights of the last `tail` keys (zero for keys after the row).  Any output may be NULL. */
+int selective_flash_attn_rows_ref(int64_t L, int32_t D, const uint16_t *Q, const uint16_t *K, const uint16_t *V,
+                                  float sm_scale, const int64_t *rows, int32_t n_rows, double *xo, double *lse,
+                                  double *p_tail, int32_t tail);
+
 /* Section 3.1.2 (heavy hitters and recent window) + Algorithm 1 line 3.  For every unit u the score of
  * prompt token i is the binary32 sum, query heads in ascending order, of the rep rows
  * A_cumul[(u*rep + h)*L + i].  Kept tokens: the n_rw[u] last prompt tokens (recent window) and, of the

@@ -38,7 +38,7 @@ def lib():
         for name in ("ref_check_shape", "kv_quantize_pack_ref", "kv_append_residual_ref",
                      "kv_flush_residual_ref", "minikv_decode_attn_ref", "ref_unpack_codes", "ref_dequant",
                      "ref_k_meta_pos", "kv_select_hh_rw_ref", "kv_pyramid_budget_ref",
-                     "selective_flash_attn_ref", "ref_pt_check_shape", "kv_quantize_pack_pt_ref",
+                     "selective_flash_attn_ref", "selective_flash_attn_rows_ref", "ref_pt_check_shape", "kv_quantize_pack_pt_ref",
                      "minikv_decode_attn_pt_ref", "ref_pt_unpack_codes"):
             getattr(_lib, name).restype = C.c_int
         _lib.ref_pt_token_bytes.restype = C.c_size_t
@@ -150,6 +150,24 @@ def selective_flash_attn(Q, K, V, sm_scale):
     if rc:
         raise RuntimeError("selective_flash_attn_ref failed: %d" % rc)
     return xo16, xo64, lse, acc
+
+
+def selective_flash_attn_rows(Q, K, V, sm_scale, rows, tail=0):
+    """Q, K, V float16 [L, D] of one head; rows: query positions -> (X_O float64 [n, D], lse float64 [n],
+    weights of the last `tail` keys float64 [n, tail])."""
+    Q, K, V = _f16(Q), _f16(K), _f16(V)
+    L, D = Q.shape
+    rows = np.ascontiguousarray(rows, np.int64)
+    n = rows.shape[0]
+    xo = np.zeros((n, D), np.float64)
+    lse = np.zeros((n,), np.float64)
+    pt = np.zeros((n, max(tail, 1)), np.float64)
+    rc = lib().selective_flash_attn_rows_ref(C.c_int64(L), C.c_int32(D), _p(Q), _p(K), _p(V), C.c_float(sm_scale),
+                                             _p(rows), C.c_int32(n), _p(xo), _p(lse), _p(pt) if tail else None,
+                                             C.c_int32(tail))
+    if rc:
+        raise RuntimeError("selective_flash_attn_rows_ref failed: %d" % rc)
+    return xo, lse, pt[:, :tail]
 
 
 def select_hh_rw(A_cumul, n_hh, n_rw, rep=1, idx_stride=None):

@@ -190,3 +190,37 @@ def test_prefill_select_quantize_decode_chain(g):
     g.assert_cache_bit_exact(gc, rc, what=("Kc", "Ks", "Kz", "Vc", "Vs", "Vz", "q_len", "r_len"))
     want, _, _ = ref.decode_attn(rc, g.to_np(qn), sm)
     assert np.max(np.abs(g.to_np(out).astype(np.float64) - want)) <= 2e-3
+
+
+def test_benchmarked_shape_on_sampled_rows_and_late_columns(g):
+    """The shape bench.py times (one sequence of 32768 tokens, 32 query / 8 KV heads): the whole matrix is out of
+    the oracle's reach, so query rows are sampled (tile edges, the first and last rows, random ones) for X_O and
+    LSE, the cumulative scores of the last 96 columns are rebuilt from the oracle's weights of the last 96 rows,
+    and every head must satisfy what holds at any size: the column sums add up to L, the first column gets at
+    least its own row, the last column exactly the last row's own weight."""
+    from oracle import ref
+    B, Hq, Hkv, L = 1, 32, 8, 32768
+    sm = 1.0 / math.sqrt(128)
+    Q, K, V = W.make_prefill_inputs(B, Hq, Hkv, L, 1013, device="cuda")
+    xo, lse, acc = run_gpu(Q, K, V, sm)
+    assert torch.isfinite(xo).all() and torch.isfinite(lse).all() and torch.isfinite(acc).all()
+    accd = acc.double()
+    assert torch.allclose(accd.sum(-1), torch.full((B, Hq), float(L), dtype=torch.float64, device="cuda"), rtol=1e-4)
+    assert (accd[..., 0] >= 1.0 - 1e-3).all()
+    rng = np.random.default_rng(5)
+    tail = 96
+    for hq in (0, 13, 31):
+        hk = hq // (Hq // Hkv)
+        q, k, v = g.to_np(Q[0, hq]), g.to_np(K[0, hk]), g.to_np(V[0, hk])
+        rows = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, 129, 8191, 8192, 16383, 16384, L - 129, L - 128, L - 2, L - 1],
+                                         rng.integers(0, L, 12)])).astype(np.int64)
+        want_o, want_l, _ = ref.selective_flash_attn_rows(q, k, v, sm, rows)
+        got_o = g.to_np(xo[0, hq]).astype(np.float64)[rows]
+        got_l = g.to_np(lse[0, hq]).astype(np.float64)[rows]
+        assert np.max(np.abs(got_o - want_o)) <= TOL_O
+        assert np.max(np.abs(got_l - want_l)) <= TOL_LSE
+        late = np.arange(L - tail, L, dtype=np.int64)
+        _, _, pt = ref.selective_flash_attn_rows(q, k, v, sm, late, tail=tail)
+        want_a = pt.sum(axis=0)
+        got_a = g.to_np(acc[0, hq]).astype(np.float64)[L - tail:]
+        assert np.all(np.abs(got_a - want_a) <= RTOL_A * np.abs(want_a) + ATOL_A)

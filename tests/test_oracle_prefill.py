@@ -103,3 +103,28 @@ def test_a_transposed_operand_or_a_missing_mask_would_show():
     S = np.einsum("bhid,bhjd->bhij", Q.astype(np.float64), K.astype(np.float64)) * sm
     full = np.exp(S - S.max(-1, keepdims=True)); full /= full.sum(-1, keepdims=True)
     assert np.max(np.abs(acc - full.sum(-2))) > 1e-3         # no causal mask
+
+
+def test_rows_view_equals_the_full_oracle_and_numpy(ref):
+    """selective_flash_attn_rows (the per-row form used at full size) against the full oracle and against a
+    numpy softmax: outputs, lse, and the cumulative score of late columns rebuilt from the rows' tail weights."""
+    from scipy.special import softmax, logsumexp
+    rng = np.random.default_rng(17)
+    L, D, tail = 150, 128, 40
+    Q = rng.standard_normal((L, D)).astype(np.float16)
+    K = rng.standard_normal((L, D)).astype(np.float16)
+    V = rng.standard_normal((L, D)).astype(np.float16)
+    sm = 0.11
+    _, xo64, lse64, acc64 = ref.selective_flash_attn(Q[None, None], K[None, None], V[None, None], sm)
+    rows = np.array([0, 1, 63, 64, 127, 128, 149], np.int64)
+    xo, lse, _ = ref.selective_flash_attn_rows(Q, K, V, sm, rows)
+    assert np.max(np.abs(xo - xo64[0, 0, rows])) <= 1e-12 and np.max(np.abs(lse - lse64[0, 0, rows])) <= 1e-12
+    for r, i in enumerate(rows):
+        s = float(np.float32(sm)) * (K[: i + 1].astype(np.float64) @ Q[i].astype(np.float64))
+        assert abs(lse[r] - logsumexp(s)) <= 1e-12
+        assert np.max(np.abs(xo[r] - softmax(s) @ V[: i + 1].astype(np.float64))) <= 1e-12
+    # the last `tail` columns only receive weight from the last `tail` rows
+    late = np.arange(L - tail, L, dtype=np.int64)
+    _, _, pt = ref.selective_flash_attn_rows(Q, K, V, sm, late, tail=tail)
+    assert np.max(np.abs(pt.sum(axis=0) - acc64[0, 0, L - tail:])) <= 1e-12
+    assert np.all(np.triu(pt, 1) == 0)                     # a row gives nothing to the keys after it
