@@ -175,17 +175,16 @@ __device__ inline float pt_wave_sum(float v)
 // + Kz_g * (sum_{c in g} q_c), so the codes meet the query before any scale does --; block-wide online
 // softmax; value phase, one channel per thread, the weights times the token's V scale read from LDS, the
 // zero-point term kept per token thread and reduced once at the end.
-template <int BITS, int G>
+template <int BITS, int G, int REPT>
 __global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
 {
     constexpr int CPW = 32 / BITS, NG = kD / G, W = kD / CPW;
     constexpr uint32_t MASK = (1u << BITS) - 1u;
-    __shared__ __attribute__((aligned(16))) float qs[kPtMaxRep][kD];          // q * sm_scale * log2(e)
-    __shared__ float qsum[kPtMaxRep][NG];                                     // its sums over the channel groups
-    __shared__ __attribute__((aligned(16))) float wgt[kPtMaxRep][NG][kPtSB];  // weight * V scale of the block's tokens
-    __shared__ float red[4][kPtMaxRep];
-    __shared__ float comb[kPtMaxRep][kD];
-    __shared__ float zsum[kPtMaxRep][NG];
+    __shared__ float qsum[REPT][NG];                                     // sums of q over the channel groups
+    __shared__ __attribute__((aligned(16))) float wgt[REPT][NG][kPtSB];  // weight * V scale of the block's tokens
+    __shared__ float red[4][REPT];
+    __shared__ float comb[REPT][kD];
+    __shared__ float zsum[REPT][NG];
 
     const int u = blockIdx.y, ch = blockIdx.x, tid = threadIdx.x, rep = a.rep;
     const int b = u / a.Hkv, kvh = u % a.Hkv;
@@ -194,13 +193,15 @@ __global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
     const int t_begin = ch * a.chunk, t_end = min(T, t_begin + a.chunk);
     if (t_begin >= t_end) return;                       // the merge kernel skips this slot
 
-    for (int i = tid; i < rep * kD; i += 256)
-        qs[i / kD][i % kD] = pt_h2f(a.q[(size_t)(bq0 + i / kD) * kD + i % kD]) * a.c1;
-    __syncthreads();
-    if (tid < rep * NG) {
+    // The query rows are read through wave-uniform loads (they end up in scalar registers and feed the
+    // multiply-adds as fp16 operands); heads beyond rep read the unit's last head and are never written out.
+    const __half2 *qrow[REPT];
+#pragma unroll
+    for (int h = 0; h < REPT; h++) qrow[h] = reinterpret_cast<const __half2 *>(a.q + (size_t)(bq0 + min(h, rep - 1)) * kD);
+    if (tid < REPT * NG) {
         const int h = tid / NG, g = tid % NG;
         float s = 0.f;
-        for (int c = 0; c < G; c++) s += qs[h][g * G + c];
+        for (int c = 0; c < G; c++) s += pt_h2f(a.q[(size_t)(bq0 + min(h, rep - 1)) * kD + g * G + c]);
         qsum[h][g] = s;
     }
     __syncthreads();
@@ -210,33 +211,56 @@ __global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
     const uint16_t *Ks = a.Ks + (size_t)u * a.Tcap * NG, *Kz = a.Kz + (size_t)u * a.Tcap * NG;
     const uint16_t *Vs = a.Vs + (size_t)u * a.Tcap * NG, *Vz = a.Vz + (size_t)u * a.Tcap * NG;
 
-    float m[kPtMaxRep], l[kPtMaxRep], o[kPtMaxRep], pz[kPtMaxRep][NG];
+    float m[REPT], l[REPT], o[REPT], pz[REPT][NG];
 #pragma unroll
-    for (int h = 0; h < kPtMaxRep; h++) {
+    for (int h = 0; h < REPT; h++) {
         m[h] = -1e30f; l[h] = 0.f; o[h] = 0.f;
 #pragma unroll
         for (int g = 0; g < NG; g++) pz[h][g] = 0.f;
     }
     const int c = tid & (kD - 1), half = tid >> 7, cg = c / G;
 
-    for (int ts = t_begin; ts < t_end; ts += kPtSB) {
-        // ---- scores of token ts + tid
-        const int t = ts + tid;
-        const bool valid = t < t_end;
-        const int tc = valid ? t : t_end - 1;
-        float s[kPtMaxRep];
+    // The words of a block are requested well before they are used: the key words, scales and zero-points
+    // of the NEXT block right after the score phase has consumed this block's, the value words of this
+    // block before its score phase.  (A load that waits for its predecessor's data costs a full memory
+    // round trip; sixteen of those per block is what bounds a version without this.)
+    constexpr int NVW = 128 / CPW;                      // value words of one thread and block
+    uint4 kq[W / 4];
+    uint16_t ksr[NG], kzr[NG], vsr[NG], vzr[NG];
+    auto request_k = [&](int ts_) {
+        const int tc_ = min(ts_ + tid, t_end - 1);
+        const uint4 *kw4 = reinterpret_cast<const uint4 *>(Kc + (size_t)tc_ * W);
 #pragma unroll
-        for (int h = 0; h < kPtMaxRep; h++) s[h] = 0.f;
+        for (int i = 0; i < W / 4; i++) kq[i] = kw4[i];
+#pragma unroll
+        for (int g = 0; g < NG; g++) {
+            ksr[g] = Ks[(size_t)tc_ * NG + g]; kzr[g] = Kz[(size_t)tc_ * NG + g];
+            vsr[g] = Vs[(size_t)tc_ * NG + g]; vzr[g] = Vz[(size_t)tc_ * NG + g];
+        }
+    };
+    request_k(t_begin);
+    const int vrow_last = a.Tcap / CPW - 1;
+
+    for (int ts = t_begin; ts < t_end; ts += kPtSB) {
+        const bool valid = ts + tid < t_end;
+        uint32_t vw[NVW];                               // rows past the cache's end repeat its last row: their weights are 0
+#pragma unroll
+        for (int i = 0; i < NVW; i++) vw[i] = Vc[(size_t)min((ts + half * 128) / CPW + i, vrow_last) * kD + c];
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- scores of token ts + tid
+        float s[REPT];
+#pragma unroll
+        for (int h = 0; h < REPT; h++) s[h] = 0.f;
+        float vs[NG], vz[NG];
         {
-            const uint4 *kw4 = reinterpret_cast<const uint4 *>(Kc + (size_t)tc * W);
-            float dot[NG][kPtMaxRep];
+            float dot[NG][REPT];
 #pragma unroll
             for (int g = 0; g < NG; g++)
 #pragma unroll
-                for (int h = 0; h < kPtMaxRep; h++) dot[g][h] = 0.f;
+                for (int h = 0; h < REPT; h++) dot[g][h] = 0.f;
 #pragma unroll
             for (int w4 = 0; w4 < W / 4; w4++) {
-                const uint4 q4 = kw4[w4];
+                const uint4 q4 = kq[w4];
                 const uint32_t ww[4] = {q4.x, q4.y, q4.z, q4.w};
 #pragma unroll
                 for (int wi = 0; wi < 4; wi++) {
@@ -250,83 +274,78 @@ __global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
                         const float k2 = (float)((ww[wi] >> (BITS * (j + 2))) & MASK);
                         const float k3 = (float)((ww[wi] >> (BITS * (j + 3))) & MASK);
 #pragma unroll
-                        for (int h = 0; h < kPtMaxRep; h++) {
-                            if (h < rep) {
-                                const float4 qq = *reinterpret_cast<const float4 *>(&qs[h][cc]);
-                                dot[g][h] += qq.x * k0 + qq.y * k1 + qq.z * k2 + qq.w * k3;
-                            }
+                        for (int h = 0; h < REPT; h++) {
+                            const __half2 qa = qrow[h][cc / 2], qb = qrow[h][cc / 2 + 1];
+                            float d = dot[g][h];                  // (fused: an fp16 operand folds into the multiply-add)
+                            d = __builtin_fmaf(__low2float(qa), k0, d);
+                            d = __builtin_fmaf(__high2float(qa), k1, d);
+                            d = __builtin_fmaf(__low2float(qb), k2, d);
+                            d = __builtin_fmaf(__high2float(qb), k3, d);
+                            dot[g][h] = d;
                         }
                     }
                 }
             }
 #pragma unroll
             for (int g = 0; g < NG; g++) {
-                const float ks = pt_h2f(Ks[(size_t)tc * NG + g]), kz = pt_h2f(Kz[(size_t)tc * NG + g]);
+                const float ks = pt_h2f(ksr[g]), kz = pt_h2f(kzr[g]);
+                vs[g] = pt_h2f(vsr[g]); vz[g] = pt_h2f(vzr[g]);
 #pragma unroll
-                for (int h = 0; h < kPtMaxRep; h++)
-                    if (h < rep) s[h] += ks * dot[g][h] + kz * qsum[h][g];
+                for (int h = 0; h < REPT; h++) s[h] += ks * dot[g][h] + kz * qsum[h][g];
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        if (ts + kPtSB < t_end) request_k(ts + kPtSB);
+        __builtin_amdgcn_sched_barrier(0);
         // ---- block max, weights, block sum
 #pragma unroll
-        for (int h = 0; h < kPtMaxRep; h++) {
-            if (h < rep) {
-                s[h] = valid ? s[h] : -INFINITY;
-                const float wm = pt_wave_max(s[h]);
-                if ((tid & 63) == 0) red[tid >> 6][h] = wm;
-            }
+        for (int h = 0; h < REPT; h++) {
+            s[h] = valid ? s[h] * a.c1 : -INFINITY;       // base-2 domain
+            const float wm = pt_wave_max(s[h]);
+            if ((tid & 63) == 0) red[tid >> 6][h] = wm;
         }
         __syncthreads();
-        float scale[kPtMaxRep], p[kPtMaxRep];
+        float scale[REPT], p[REPT];
 #pragma unroll
-        for (int h = 0; h < kPtMaxRep; h++) {
-            if (h < rep) {
-                const float bm = fmaxf(fmaxf(red[0][h], red[1][h]), fmaxf(red[2][h], red[3][h]));
-                const float mn = fmaxf(m[h], bm);
-                scale[h] = exp2f(m[h] - mn);
-                m[h] = mn;
-                p[h] = exp2f(s[h] - mn);                // exp2(-inf) = 0 for the masked tail
-            }
+        for (int h = 0; h < REPT; h++) {
+            const float bm = fmaxf(fmaxf(red[0][h], red[1][h]), fmaxf(red[2][h], red[3][h]));
+            const float mn = fmaxf(m[h], bm);
+            scale[h] = exp2f(m[h] - mn);
+            m[h] = mn;
+            p[h] = exp2f(s[h] - mn);                    // exp2(-inf) = 0 for the masked tail
         }
         __syncthreads();
-        {
-            float vs[NG], vz[NG];
 #pragma unroll
-            for (int g = 0; g < NG; g++) { vs[g] = pt_h2f(Vs[(size_t)tc * NG + g]); vz[g] = pt_h2f(Vz[(size_t)tc * NG + g]); }
+        for (int h = 0; h < REPT; h++) {
+            const float ws = pt_wave_sum(p[h]);
+            if ((tid & 63) == 0) red[tid >> 6][h] = ws;
 #pragma unroll
-            for (int h = 0; h < kPtMaxRep; h++) {
-                if (h < rep) {
-                    const float ws = pt_wave_sum(p[h]);
-                    if ((tid & 63) == 0) red[tid >> 6][h] = ws;
-#pragma unroll
-                    for (int g = 0; g < NG; g++) {
-                        wgt[h][g][tid] = p[h] * vs[g];
-                        pz[h][g] = pz[h][g] * scale[h] + p[h] * vz[g];
-                    }
-                }
+            for (int g = 0; g < NG; g++) {
+                wgt[h][g][tid] = p[h] * vs[g];
+                pz[h][g] = pz[h][g] * scale[h] + p[h] * vz[g];
             }
         }
         __syncthreads();
 #pragma unroll
-        for (int h = 0; h < kPtMaxRep; h++) {
-            if (h < rep) {
-                l[h] = l[h] * scale[h] + (red[0][h] + red[1][h] + red[2][h] + red[3][h]);
-                o[h] *= scale[h];
-            }
+        for (int h = 0; h < REPT; h++) {
+            l[h] = l[h] * scale[h] + (red[0][h] + red[1][h] + red[2][h] + red[3][h]);
+            o[h] *= scale[h];
         }
         // ---- weighted values: thread (c, half) takes tokens [half*128, half*128 + 128) of the block
         const int nb = min(kPtSB, t_end - ts);          // multiple of 16
-        for (int tt = half * 128; tt < min(nb, half * 128 + 128); tt += CPW) {
-            const uint32_t word = Vc[(size_t)((ts + tt) / CPW) * kD + c];
 #pragma unroll
-            for (int j = 0; j < CPW; j += 4) {
-                const float v0 = (float)((word >> (BITS * j)) & MASK), v1 = (float)((word >> (BITS * (j + 1))) & MASK);
-                const float v2 = (float)((word >> (BITS * (j + 2))) & MASK), v3 = (float)((word >> (BITS * (j + 3))) & MASK);
+        for (int i = 0; i < NVW; i++) {
+            const int tt = half * 128 + i * CPW;
+            if (tt < nb) {
+                const uint32_t word = vw[i];
 #pragma unroll
-                for (int h = 0; h < kPtMaxRep; h++) {
-                    if (h < rep) {
+                for (int j = 0; j < CPW; j += 4) {
+                    const float v0 = (float)((word >> (BITS * j)) & MASK), v1 = (float)((word >> (BITS * (j + 1))) & MASK);
+                    const float v2 = (float)((word >> (BITS * (j + 2))) & MASK), v3 = (float)((word >> (BITS * (j + 3))) & MASK);
+#pragma unroll
+                    for (int h = 0; h < REPT; h++) {
                         const float4 w4 = *reinterpret_cast<const float4 *>(&wgt[h][cg][tt + j]);
-                        o[h] += w4.x * v0 + w4.y * v1 + w4.z * v2 + w4.w * v3;
+                        o[h] = __builtin_fmaf(w4.x, v0, __builtin_fmaf(w4.y, v1, __builtin_fmaf(w4.z, v2, __builtin_fmaf(w4.w, v3, o[h]))));
                     }
                 }
             }
@@ -335,27 +354,31 @@ __global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
     }
 
     // ---- zero-point term: sum over the token threads, per (head, channel group)
-    if (tid < kPtMaxRep * NG) zsum[tid / NG][tid % NG] = 0.f;
+    if (tid < REPT * NG) zsum[tid / NG][tid % NG] = 0.f;
     __syncthreads();
 #pragma unroll
-    for (int h = 0; h < kPtMaxRep; h++) {
-        if (h < rep) {
+    for (int h = 0; h < REPT; h++) {
 #pragma unroll
-            for (int g = 0; g < NG; g++) {
-                const float wsum = pt_wave_sum(pz[h][g]);
-                if ((tid & 63) == 0) atomicAdd(&zsum[h][g], wsum);
+        for (int g = 0; g < NG; g++) {
+            const float wsum = pt_wave_sum(pz[h][g]);
+            if ((tid & 63) == 0) atomicAdd(&zsum[h][g], wsum);
+        }
+    }
+    if (half == 1) {
+#pragma unroll
+        for (int h = 0; h < REPT; h++) comb[h][c] = o[h];
+    }
+    __syncthreads();
+    if (half == 0) {
+#pragma unroll
+        for (int h = 0; h < REPT; h++) {
+            if (h < rep) {
+                float *pp = a.ws + ((size_t)(bq0 + h) * a.nchunk + ch) * kPartialStride;
+                pp[4 + c] = o[h] + comb[h][c] + zsum[h][cg];
+                if (c == 0) { pp[0] = m[h]; pp[1] = l[h]; }
             }
         }
     }
-    if (half == 1)
-        for (int h = 0; h < rep; h++) comb[h][c] = o[h];
-    __syncthreads();
-    if (half == 0)
-        for (int h = 0; h < rep; h++) {
-            float *pp = a.ws + ((size_t)(bq0 + h) * a.nchunk + ch) * kPartialStride;
-            pp[4 + c] = o[h] + comb[h][c] + zsum[h][cg];
-            if (c == 0) { pp[0] = m[h]; pp[1] = l[h]; }
-        }
 }
 
 // One workgroup of 128 threads per query row: combine the partials of the chunks that hold tokens.
@@ -422,16 +445,26 @@ static int pt_launch_quantize(const PtQuantArgs &a, int G, dim3 grid, int units,
     return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
 }
 
-template <int BITS>
-static int pt_launch_decode(const PtDecArgs &a, int G, dim3 grid, hipStream_t st)
+template <int BITS, int REPT>
+static int pt_launch_decode_g(const PtDecArgs &a, int G, dim3 grid, hipStream_t st)
 {
     switch (G) {
-    case 32: hipLaunchKernelGGL((decode_pt_kernel<BITS, 32>), grid, dim3(256), 0, st, a); break;
-    case 64: hipLaunchKernelGGL((decode_pt_kernel<BITS, 64>), grid, dim3(256), 0, st, a); break;
-    case 128: hipLaunchKernelGGL((decode_pt_kernel<BITS, 128>), grid, dim3(256), 0, st, a); break;
+    case 32: hipLaunchKernelGGL((decode_pt_kernel<BITS, 32, REPT>), grid, dim3(256), 0, st, a); break;
+    case 64: hipLaunchKernelGGL((decode_pt_kernel<BITS, 64, REPT>), grid, dim3(256), 0, st, a); break;
+    case 128: hipLaunchKernelGGL((decode_pt_kernel<BITS, 128, REPT>), grid, dim3(256), 0, st, a); break;
     default: return MINIKV_EUNSUPPORTED;
     }
     return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
+}
+
+// heads per unit rounded up to 1, 2, 4 or 8 (the spare ones repeat the last head and are not written)
+template <int BITS>
+static int pt_launch_decode(const PtDecArgs &a, int G, dim3 grid, hipStream_t st)
+{
+    if (a.rep <= 1) return pt_launch_decode_g<BITS, 1>(a, G, grid, st);
+    if (a.rep <= 2) return pt_launch_decode_g<BITS, 2>(a, G, grid, st);
+    if (a.rep <= 4) return pt_launch_decode_g<BITS, 4>(a, G, grid, st);
+    return pt_launch_decode_g<BITS, 8>(a, G, grid, st);
 }
 
 }  // namespace minikv
