@@ -344,6 +344,26 @@ def main():
             "frac_of_hbm_peak": round(sel_bytes / sel_us / 1e3 / HBM_PEAK_GBS, 3),
         }
         del A, sel_idx, sel_ws
+        # ... and on a few long prompts (the ragged configuration's shape: 8 units of 4 heads, 131072 tokens, 40 %
+        # kept), where the selection runs with several workgroups per unit
+        Ul, Ll, kl = 8, 131072, 26208
+        A = W.make_scores(Ul * rep, Ll, seed=w.seed + 6, device="cuda", kind="attention")
+        n_hh = torch.full((Ul,), kl, dtype=torch.int32, device="cuda")
+        sel_idx = torch.empty(Ul, 2 * kl, dtype=torch.int32, device="cuda")
+        sel_n = torch.empty(Ul, dtype=torch.int32, device="cuda")
+        sel_ws = torch.empty(max(api.kv_select_workspace_bytes(Ul, rep, Ll), 16), dtype=torch.uint8, device="cuda")
+        for i in range(2 + reps):
+            if i == 2:
+                a.record()
+            api.kv_select_hh_rw(Ul, rep, Ll, A, n_hh, n_hh, sel_idx, 2 * kl, sel_n, sel_ws)
+        b.record()
+        torch.cuda.synchronize()
+        long_us = a.elapsed_time(b) * 1e3 / reps
+        long_bytes = W.selection_bytes(Ul, rep, Ll, sel_n.cpu().tolist())
+        result["select_hh_rw"]["few_long_prompts"] = {
+            "units": Ul, "rep": rep, "L": Ll, "us": round(long_us, 2), "bytes": long_bytes,
+            "GB/s": round(long_bytes / long_us / 1e3, 1)}
+        del A, sel_idx, sel_ws
 
         # prefill attention with cumulative scores (both passes), one sequence with this workload's heads and
         # context, and the longest prompt of the paper's kernel table (8192 tokens, 32 heads)

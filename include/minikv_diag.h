@@ -22,6 +22,11 @@ int minikv_stream_read_probe(const void *src, size_t bytes, uint32_t *sums, void
  * the fast range.  Synchronous (a blocking 4-byte copy to the host); count is a HOST pointer. */
 int minikv_diag_redo_count(const minikv_shape *shape, const void *workspace, int32_t *count);
 
+/* Which kernels kv_select_hh_rw launches (process-wide): 0 = chosen by shape (default), 1 = always one workgroup
+ * per unit, 2 = several workgroups per unit whenever the prompt has at most 1024 chunks of 4096 tokens.  Both
+ * give the same positions; the parity tests run each.  MINIKV_EINVAL for any other value. */
+int         minikv_diag_select_path(int path);
+
 /* Selects the kernel minikv_decode_attn launches (process-wide):
  *   0 = default, 1 = a plain scalar-loop fp32 kernel (two launches) kept as a second GPU implementation of
  *   Algorithm 1 lines 17-19 for cross-checks, 3 = the default kernel by its own number.

@@ -61,6 +61,8 @@ def lib():
         l.minikv_strvariant.argtypes = [C.c_int]
         l.minikv_set_variant.restype = C.c_int
         l.minikv_set_variant.argtypes = [C.c_int]
+        l.minikv_diag_select_path.restype = C.c_int
+        l.minikv_diag_select_path.argtypes = [C.c_int]
         l.minikv_buffer_bytes.restype = C.c_size_t
         l.minikv_buffer_bytes.argtypes = [C.POINTER(MinikvShape), C.c_int]
         l.minikv_cache_bytes.restype = C.c_size_t
@@ -235,6 +237,10 @@ def minikv_diag_redo_count(shape, workspace):
     n = C.c_int32(0)
     _check(lib().minikv_diag_redo_count(C.byref(shape), _ptr(workspace), C.byref(n)), "minikv_diag_redo_count")
     return int(n.value)
+
+
+def minikv_diag_select_path(path):
+    _check(lib().minikv_diag_select_path(int(path)), "minikv_diag_select_path")
 
 
 def minikv_set_variant(v):

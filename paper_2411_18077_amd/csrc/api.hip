@@ -191,8 +191,7 @@ int selective_flash_attn(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, const mi
 
 size_t kv_select_workspace_bytes(int32_t units, int32_t rep, int64_t L)
 {
-    if (units <= 0 || rep <= 1 || L <= 0) return 0;
-    return (size_t)units * (size_t)L * sizeof(uint32_t);        // one summed-score key per (unit, token)
+    return select_workspace_bytes(units, rep, L);
 }
 
 int kv_select_hh_rw(int32_t units, int32_t rep, int64_t L, const float *A_cumul, const int32_t *n_hh,
@@ -204,7 +203,7 @@ int kv_select_hh_rw(int32_t units, int32_t rep, int64_t L, const float *A_cumul,
     if (!n_hh || !n_rw || !idx || !n_tok || ((uintptr_t)idx & 3u) || ((uintptr_t)n_tok & 3u)) return MINIKV_EINVAL;
     if (L > 0 && (!A_cumul || ((uintptr_t)A_cumul & 3u))) return MINIKV_EINVAL;
     const size_t need = kv_select_workspace_bytes(units, rep, L);
-    if (need && (!workspace || ((uintptr_t)workspace & 3u))) return MINIKV_EINVAL;
+    if (need && (!workspace || ((uintptr_t)workspace & 15u))) return MINIKV_EINVAL;
     if (workspace_bytes < need) return MINIKV_EWORKSPACE;
     return launch_select(units, rep, L, A_cumul, n_hh, n_rw, idx, idx_stride, n_tok, workspace,
                          (hipStream_t)stream);
@@ -236,6 +235,11 @@ int minikv_diag_redo_count(const minikv_shape *s, const void *workspace, int32_t
     if (validate_shape(s) != MINIKV_OK || !workspace || !count) return MINIKV_EINVAL;
     const int *p = reinterpret_cast<const int *>(workspace) + 3 * ws_units(*s) + kMaxStreamWaves;
     return hipMemcpy(count, p, sizeof(int32_t), hipMemcpyDeviceToHost) == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
+}
+
+int minikv_diag_select_path(int path)
+{
+    return set_select_path(path) ? MINIKV_OK : MINIKV_EINVAL;
 }
 
 int minikv_set_variant(int variant)

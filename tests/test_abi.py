@@ -97,10 +97,18 @@ def test_selection_arguments_are_checked_on_the_host(api):
     assert call(4, 1, 64, P(0x1002), *ok[1:4], 64, ok[4], None, 0) == -1             # misaligned scores
     assert call(4, 1, 64, ok[0], None, *ok[2:4], 64, ok[4], None, 0) == -1
     assert call(4, 1, 64, *ok[:4], -1, ok[4], None, 0) == -1
-    assert call(4, 4, 64, *ok[:4], 64, ok[4], None, 0) == -1                         # rep > 1 needs a workspace
-    assert call(4, 4, 64, *ok[:4], 64, ok[4], P(0x1000), 4 * 64 * 4 - 1) == -3
-    assert api.kv_select_workspace_bytes(4, 4, 64) == 4 * 64 * 4
-    assert api.kv_select_workspace_bytes(4, 1, 64) == 0 and api.kv_select_workspace_bytes(0, 4, 64) == 0
+    need4, need1 = api.kv_select_workspace_bytes(4, 4, 64), api.kv_select_workspace_bytes(4, 1, 64)
+    assert call(4, 4, 64, *ok[:4], 64, ok[4], None, 0) == -1                         # a workspace is needed
+    assert call(4, 1, 64, *ok[:4], 64, ok[4], None, 0) == -1
+    assert call(4, 4, 64, *ok[:4], 64, ok[4], P(0x1000), need4 - 1) == -3
+    assert call(4, 1, 64, *ok[:4], 64, ok[4], P(0x1000), need1 - 1) == -3
+    assert call(4, 1, 64, *ok[:4], 64, ok[4], P(0x1004), need1) == -1                # workspace not 16-byte aligned
+    # summed-score keys (several heads only) + per 4096-token chunk: candidate list, histogram, counts + unit histogram
+    assert need4 - need1 == 4 * 64 * 4 and need1 == 4 * (4096 + 1024 + 4 + 2048) * 4
+    assert api.kv_select_workspace_bytes(0, 4, 64) == 0 and api.kv_select_workspace_bytes(4, 4, 0) == 0
+    # prompts beyond 1024 chunks take the one-workgroup-per-unit kernel, which keeps only the keys
+    assert api.kv_select_workspace_bytes(2, 4, 4096 * 1024 + 1) == 2 * (4096 * 1024 + 1) * 4
+    assert api.kv_select_workspace_bytes(2, 1, 4096 * 1024 + 1) == 0
 
 
 def test_pyramid_budget_is_host_arithmetic_and_matches_the_oracle(api):

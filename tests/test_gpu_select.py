@@ -18,6 +18,15 @@ def g():
     return gpu_common
 
 
+@pytest.fixture(autouse=True, params=[0, 1, 2], ids=["by-shape", "one-workgroup-per-unit", "chunked"])
+def select_path(request):
+    """Every test runs with the kernels chosen by shape and with each of the two sets forced."""
+    from paper_2411_18077_amd import api
+    api.minikv_diag_select_path(request.param)
+    yield request.param
+    api.minikv_diag_select_path(0)
+
+
 def run_gpu(A, n_hh, n_rw, rep, idx_stride):
     """A: cuda float32 [U*rep, L].  Returns (idx [U, idx_stride] with -1 where nothing was written, n_tok)."""
     from paper_2411_18077_amd import api
