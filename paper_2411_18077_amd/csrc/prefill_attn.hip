@@ -235,35 +235,53 @@ __global__ __launch_bounds__(256, 2) void prefill_fwd_kernel(PrefillArgs a)
             const float alpha = __builtin_amdgcn_exp2f((m - mx) * c);   // m = -inf at the first tile: alpha = 0
             m = mx;
             const float mc = -mx * c;
-            float psum = 0.0f;
-            half8 pb[2][2];                            // B operands of O^T += V^T P^T, 16 keys each
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][i], c, mc));
-                    psum += p;
-                    pb[t][i >> 3][i & 7] = (_Float16)p;
-                }
-            l = l * alpha + psum;
             if (__any(alpha != 1.0f)) {
 #pragma unroll
                 for (int db = 0; db < 4; ++db)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
             }
+            // Output products in four steps of 16 keys (step q: keys 32 (q>>1) + 16 (q&1) + 4 g + {0..3} and the
+            // same + 8, the accumulator's own order).  The V^T fragments of step q+1 are requested and the
+            // weights of step q+1 computed while the four products of step q run.
+            float psum = 0.0f;
+            auto weights = [&](int q) -> half8 {           // B operand of step q: exp2 of its eight scores
+                half8 pb;
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+                for (int j = 0; j < 8; ++j) {
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[q >> 1][(q & 1) * 8 + j], c, mc));
+                    psum += p;
+                    pb[j] = (_Float16)p;
+                }
+                return pb;
+            };
+            const _Float16 *vbase = Vc + r * kPfVRow + g * 4;
+            auto vfrag = [&](int q, int db) -> half8 {
+                const _Float16 *vp = vbase + db * 32 * kPfVRow + q * 16;
+                const half4 lo = *(const half4 *)vp, hi = *(const half4 *)(vp + 8);
+                return half8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            };
+            half8 vf[4], vn[4], pb = weights(0), pn;
 #pragma unroll
-                for (int sx = 0; sx < 2; ++sx)
+            for (int db = 0; db < 4; ++db) vf[db] = vfrag(0, db);
 #pragma unroll
-                    for (int db = 0; db < 4; ++db) {
-                        // keys of this step in accumulator order: 32 t + 16 sx + 4 g + {0..3} and the same + 8
-                        const _Float16 *vp = Vc + (db * 32 + r) * kPfVRow + t * 32 + sx * 16 + g * 4;
-                        const half4 lo = *(const half4 *)vp, hi = *(const half4 *)(vp + 8);
-                        const half8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                        o[db] = mfma32(vf, pb[t][sx], o[db]);
-                    }
+            for (int q = 0; q < 4; ++q) {
+                if (q < 3) {
+#pragma unroll
+                    for (int db = 0; db < 4; ++db) vn[db] = vfrag(q + 1, db);
+                }
+                __builtin_amdgcn_sched_barrier(0);         // (the requests stay above the products)
+                if (q < 3) pn = weights(q + 1);
+#pragma unroll
+                for (int db = 0; db < 4; ++db) o[db] = mfma32(vf[db], pb, o[db]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (q < 3) {
+                    pb = pn;
+#pragma unroll
+                    for (int db = 0; db < 4; ++db) vf[db] = vn[db];
+                }
+            }
+            l = l * alpha + psum;
         } else if (n + 1 < ntiles) {                   // a wave that skips the tile still moves its share of the next one
             kr = load_tile(krs, k_lane, (n + 1) * kKTileBytes);
             vr = load_tile_vt(vrs, v_lane, (n + 1) * kVTileBytes, row_bytes);
