@@ -170,18 +170,40 @@ __device__ inline float pt_wave_sum(float v)
     return v;
 }
 
+// A 16-bit half of a packed word holds NF = 16 / BITS codes.  A code field that lies inside bits 0..9 of its
+// half is, masked in place, an fp16 SUBNORMAL: code * 2^(BITS*pos) * 2^-24 -- so one v_and_b32 "converts" two
+// codes (one per half) and one v_dot2_f32_f16 multiplies them with two fp16 operands and adds both products
+// in binary32 (fp16 subnormals are honoured by that instruction).  Fields at positions 0 .. PMAX-1 are taken
+// from the word as it is, the others from the word shifted right by SH2 bits, which brings them to positions
+// NF-PMAX .. PMAX-1 ... of a field j: pt_field_pos().  Sums are kept per position and scaled once at the end.
+template <int BITS> struct PtFields {
+    static constexpr int NF = 16 / BITS;                 // fields per half-word
+    static constexpr int PMAX = 10 / BITS;               // positions whose field fits into the fp16 mantissa
+    static constexpr int SH2 = BITS * (NF - PMAX);       // shift that brings the upper fields down
+    static constexpr uint32_t M0 = ((1u << BITS) - 1u) * 0x00010001u;
+    static_assert(NF <= 2 * PMAX, "two looks at a word reach every field");
+    __device__ static constexpr int pos(int j) { return j < PMAX ? j : j - (NF - PMAX); }
+    // 2^(24 - BITS*pos): what a sum over position pos is multiplied by
+    __device__ static constexpr float unscale(int p) { return 16777216.0f / (float)(1u << (BITS * p)); }
+};
+typedef _Float16 pt_h2 __attribute__((ext_vector_type(2)));
+
 // One workgroup = one (unit, chunk of tokens), all query heads of the unit.  Per inner block of 256 tokens:
 // score phase, one token per thread -- sum_c q_c * (code * Ks + Kz) = sum_g Ks_g * (sum_{c in g} q_c code_c)
-// + Kz_g * (sum_{c in g} q_c), so the codes meet the query before any scale does --; block-wide online
-// softmax; value phase, one channel per thread, the weights times the token's V scale read from LDS, the
-// zero-point term kept per token thread and reduced once at the end.
+// + Kz_g * (sum_{c in g} q_c), so the codes meet the query before any scale does; the query sits in LDS as
+// the fp16 pairs (channel c0 + j, channel c0 + NF + j) that the two halves of a word's field j hold --;
+// block-wide online softmax; value phase, one channel per thread, the weights times the token's V scale in LDS
+// as fp16 pairs (token t0 + j, token t0 + NF + j) in the same way; the zero-point term kept per token thread
+// and reduced once at the end.
 template <int BITS, int G, int REPT>
-__global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
+__global__ __launch_bounds__(256, 2) void decode_pt_kernel(PtDecArgs a)
 {
-    constexpr int CPW = 32 / BITS, NG = kD / G, W = kD / CPW;
-    constexpr uint32_t MASK = (1u << BITS) - 1u;
+    typedef PtFields<BITS> F;
+    constexpr int CPW = 32 / BITS, NG = kD / G, W = kD / CPW, NF = F::NF, NP = F::PMAX;
+    constexpr int NPAIR = kPtSB / 2;                                     // weight pairs of a block
     __shared__ float qsum[REPT][NG];                                     // sums of q over the channel groups
-    __shared__ __attribute__((aligned(16))) float wgt[REPT][NG][kPtSB];  // weight * V scale of the block's tokens
+    __shared__ __attribute__((aligned(16))) pt_h2 qp[kD / 2][REPT];      // query pairs, by (word, field)
+    __shared__ __attribute__((aligned(16))) pt_h2 wp[NG][NPAIR][REPT];   // weight * V scale pairs, by (word, field)
     __shared__ float red[4][REPT];
     __shared__ float comb[REPT][kD];
     __shared__ float zsum[REPT][NG];
@@ -193,11 +215,15 @@ __global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
     const int t_begin = ch * a.chunk, t_end = min(T, t_begin + a.chunk);
     if (t_begin >= t_end) return;                       // the merge kernel skips this slot
 
-    // The query rows are read through wave-uniform loads (they end up in scalar registers and feed the
-    // multiply-adds as fp16 operands); heads beyond rep read the unit's last head and are never written out.
-    const __half2 *qrow[REPT];
-#pragma unroll
-    for (int h = 0; h < REPT; h++) qrow[h] = reinterpret_cast<const __half2 *>(a.q + (size_t)(bq0 + min(h, rep - 1)) * kD);
+    // heads beyond rep read the unit's last head and are never written out
+    for (int i = tid; i < (kD / 2) * REPT; i += 256) {
+        const int h = i % REPT, pi = i / REPT, w = pi / NF, j = pi % NF;
+        const uint16_t *qr = a.q + (size_t)(bq0 + min(h, rep - 1)) * kD + w * CPW + j;
+        pt_h2 v;
+        v[0] = __builtin_bit_cast(_Float16, qr[0]);
+        v[1] = __builtin_bit_cast(_Float16, qr[NF]);
+        qp[pi][h] = v;
+    }
     if (tid < REPT * NG) {
         const int h = tid / NG, g = tid % NG;
         float s = 0.f;
@@ -219,6 +245,8 @@ __global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
         for (int g = 0; g < NG; g++) pz[h][g] = 0.f;
     }
     const int c = tid & (kD - 1), half = tid >> 7, cg = c / G;
+    // where this thread's token puts its weight: pair (tid / CPW) * NF + (tid % CPW) % NF, component (tid % CPW) / NF
+    const int my_pair = (tid / CPW) * NF + (tid % CPW) % NF, my_comp = (tid % CPW) / NF;
 
     // The words of a block are requested well before they are used: the key words, scales and zero-points
     // of the NEXT block right after the score phase has consumed this block's, the value words of this
@@ -241,8 +269,20 @@ __global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
     request_k(t_begin);
     const int vrow_last = a.Tcap / CPW - 1;
 
+    // sums over the field positions, each with its power of two
+    auto fold = [&](const float (&acc)[NP]) -> float {
+        float r = 0.f;
+#pragma unroll
+        for (int p = 0; p < NP; p++) r = __builtin_fmaf(acc[p], F::unscale(p), r);
+        return r;
+    };
+
     for (int ts = t_begin; ts < t_end; ts += kPtSB) {
         const bool valid = ts + tid < t_end;
+        // (an index the compiler cannot see through: without it the reads of the query pairs, which no iteration
+        // changes, are all moved in front of the loop and held in 64 x REPT registers)
+        int iter0 = 0;
+        asm volatile("" : "+v"(iter0));
         uint32_t vw[NVW];                               // rows past the cache's end repeat its last row: their weights are 0
 #pragma unroll
         for (int i = 0; i < NVW; i++) vw[i] = Vc[(size_t)min((ts + half * 128) / CPW + i, vrow_last) * kD + c];
@@ -253,45 +293,58 @@ __global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
         for (int h = 0; h < REPT; h++) s[h] = 0.f;
         float vs[NG], vz[NG];
         {
-            float dot[NG][REPT];
+            // the query pairs of one word at a time (scheduling barriers keep it so: left alone, the compiler
+            // requests all 64 x REPT pairs at once and spills); the other waves of the SIMD cover the LDS latency
+            // The query pairs of word wi + 1 are read from LDS while the products of word wi run.  Left alone, the
+            // compiler requests the pairs of all 64 words first and spills what comes back (scheduling barriers and
+            // plain memory barriers do not stop it: the products have no side effects and sink below them); so each
+            // word ends with empty asm statements that take its sums as operands AND clobber memory: the next
+            // reads cannot pass them, and they cannot pass the products.
+            pt_h2 qa[NF][REPT], qb[NF][REPT];
+            auto read_q = [&](pt_h2 (&dst)[NF][REPT], int wi) {
 #pragma unroll
-            for (int g = 0; g < NG; g++)
+                for (int j = 0; j < NF; j++)
 #pragma unroll
-                for (int h = 0; h < REPT; h++) dot[g][h] = 0.f;
+                    for (int h = 0; h < REPT; h++) dst[j][h] = qp[iter0 + wi * NF + j][h];
+            };
+            read_q(qa, 0);
+            float dot[REPT][NP];
 #pragma unroll
-            for (int w4 = 0; w4 < W / 4; w4++) {
-                const uint4 q4 = kq[w4];
-                const uint32_t ww[4] = {q4.x, q4.y, q4.z, q4.w};
+            for (int wi = 0; wi < W; wi++) {
+                constexpr int WG_ = G / CPW;                                   // words of one channel group
+                const int g = wi / WG_;
+                if (wi % WG_ == 0) {
 #pragma unroll
-                for (int wi = 0; wi < 4; wi++) {
-                    const int c0 = (w4 * 4 + wi) * CPW;          // first channel of this word
-                    const int g = c0 / G;                        // (a word never straddles two groups: CPW <= 16 < G)
+                    for (int h = 0; h < REPT; h++)
 #pragma unroll
-                    for (int j = 0; j < CPW; j += 4) {
-                        const int cc = c0 + j;
-                        const float k0 = (float)((ww[wi] >> (BITS * j)) & MASK);
-                        const float k1 = (float)((ww[wi] >> (BITS * (j + 1))) & MASK);
-                        const float k2 = (float)((ww[wi] >> (BITS * (j + 2))) & MASK);
-                        const float k3 = (float)((ww[wi] >> (BITS * (j + 3))) & MASK);
-#pragma unroll
-                        for (int h = 0; h < REPT; h++) {
-                            const __half2 qa = qrow[h][cc / 2], qb = qrow[h][cc / 2 + 1];
-                            float d = dot[g][h];                  // (fused: an fp16 operand folds into the multiply-add)
-                            d = __builtin_fmaf(__low2float(qa), k0, d);
-                            d = __builtin_fmaf(__high2float(qa), k1, d);
-                            d = __builtin_fmaf(__low2float(qb), k2, d);
-                            d = __builtin_fmaf(__high2float(qb), k3, d);
-                            dot[g][h] = d;
-                        }
-                    }
+                        for (int p = 0; p < NP; p++) dot[h][p] = 0.f;
                 }
-            }
+                if (wi + 1 < W) read_q(qb, wi + 1);
+                const uint4 q4 = kq[wi / 4];
+                const uint32_t word = (wi & 3) == 0 ? q4.x : (wi & 3) == 1 ? q4.y : (wi & 3) == 2 ? q4.z : q4.w;
+                const uint32_t upper = word >> F::SH2;
 #pragma unroll
-            for (int g = 0; g < NG; g++) {
-                const float ks = pt_h2f(ksr[g]), kz = pt_h2f(kzr[g]);
-                vs[g] = pt_h2f(vsr[g]); vz[g] = pt_h2f(vzr[g]);
+                for (int j = 0; j < NF; j++) {
+                    const int p = F::pos(j);
+                    const uint32_t fld = (j < F::PMAX ? word : upper) & (F::M0 << (BITS * p));
+                    const pt_h2 kk = __builtin_bit_cast(pt_h2, fld);
 #pragma unroll
-                for (int h = 0; h < REPT; h++) s[h] += ks * dot[g][h] + kz * qsum[h][g];
+                    for (int h = 0; h < REPT; h++) dot[h][p] = __builtin_amdgcn_fdot2(kk, qa[j][h], dot[h][p], false);
+                }
+#pragma unroll
+                for (int h = 0; h < REPT; h++)
+#pragma unroll
+                    for (int p = 0; p < NP; p++) asm volatile("" : "+v"(dot[h][p])::"memory");
+                if (wi % WG_ == WG_ - 1) {                                     // the group's last word: its scale and zero-point
+                    const float ks = pt_h2f(ksr[g]), kz = pt_h2f(kzr[g]);
+                    vs[g] = pt_h2f(vsr[g]); vz[g] = pt_h2f(vzr[g]);
+#pragma unroll
+                    for (int h = 0; h < REPT; h++) s[h] += ks * fold(dot[h]) + kz * qsum[h][g];
+                }
+#pragma unroll
+                for (int j = 0; j < NF; j++)
+#pragma unroll
+                    for (int h = 0; h < REPT; h++) qa[j][h] = qb[j][h];
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -317,11 +370,12 @@ __global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
         __syncthreads();
 #pragma unroll
         for (int h = 0; h < REPT; h++) {
+            // (the value phase sees p * Vs rounded to fp16; the sum of weights keeps the binary32 p)
             const float ws = pt_wave_sum(p[h]);
             if ((tid & 63) == 0) red[tid >> 6][h] = ws;
 #pragma unroll
             for (int g = 0; g < NG; g++) {
-                wgt[h][g][tid] = p[h] * vs[g];
+                reinterpret_cast<_Float16 *>(&wp[g][my_pair][h])[my_comp] = (_Float16)(p[h] * vs[g]);
                 pz[h][g] = pz[h][g] * scale[h] + p[h] * vz[g];
             }
         }
@@ -332,24 +386,45 @@ __global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
             o[h] *= scale[h];
         }
         // ---- weighted values: thread (c, half) takes tokens [half*128, half*128 + 128) of the block
-        const int nb = min(kPtSB, t_end - ts);          // multiple of 16
+        float oacc[REPT][NP];
 #pragma unroll
-        for (int i = 0; i < NVW; i++) {
-            const int tt = half * 128 + i * CPW;
-            if (tt < nb) {
-                const uint32_t word = vw[i];
+        for (int h = 0; h < REPT; h++)
 #pragma unroll
-                for (int j = 0; j < CPW; j += 4) {
-                    const float v0 = (float)((word >> (BITS * j)) & MASK), v1 = (float)((word >> (BITS * (j + 1))) & MASK);
-                    const float v2 = (float)((word >> (BITS * (j + 2))) & MASK), v3 = (float)((word >> (BITS * (j + 3))) & MASK);
+            for (int pp = 0; pp < NP; pp++) oacc[h][pp] = 0.f;
+        {
+            pt_h2 wa[NF][REPT], wb[NF][REPT];                                   // weight pairs of word i, word i + 1
+            auto read_w = [&](pt_h2 (&dst)[NF][REPT], int i) {
 #pragma unroll
-                    for (int h = 0; h < REPT; h++) {
-                        const float4 w4 = *reinterpret_cast<const float4 *>(&wgt[h][cg][tt + j]);
-                        o[h] = __builtin_fmaf(w4.x, v0, __builtin_fmaf(w4.y, v1, __builtin_fmaf(w4.z, v2, __builtin_fmaf(w4.w, v3, o[h]))));
-                    }
+                for (int j = 0; j < NF; j++)
+#pragma unroll
+                    for (int h = 0; h < REPT; h++) dst[j][h] = wp[cg][iter0 + ((half * 128) / CPW + i) * NF + j][h];
+            };
+            read_w(wa, 0);
+#pragma unroll
+            for (int i = 0; i < NVW; i++) {
+                // (words past the block's last token meet weights that are 0: no branch)
+                if (i + 1 < NVW) read_w(wb, i + 1);
+                const uint32_t word = vw[i], upper = word >> F::SH2;
+#pragma unroll
+                for (int j = 0; j < NF; j++) {
+                    const int pp = F::pos(j);
+                    const uint32_t fld = (j < F::PMAX ? word : upper) & (F::M0 << (BITS * pp));
+                    const pt_h2 vv = __builtin_bit_cast(pt_h2, fld);
+#pragma unroll
+                    for (int h = 0; h < REPT; h++) oacc[h][pp] = __builtin_amdgcn_fdot2(vv, wa[j][h], oacc[h][pp], false);
                 }
+#pragma unroll
+                for (int h = 0; h < REPT; h++)
+#pragma unroll
+                    for (int pp = 0; pp < NP; pp++) asm volatile("" : "+v"(oacc[h][pp])::"memory");
+#pragma unroll
+                for (int j = 0; j < NF; j++)
+#pragma unroll
+                    for (int h = 0; h < REPT; h++) wa[j][h] = wb[j][h];
             }
         }
+#pragma unroll
+        for (int h = 0; h < REPT; h++) o[h] += fold(oacc[h]);
         __syncthreads();
     }
 
@@ -381,22 +456,44 @@ __global__ __launch_bounds__(256) void decode_pt_kernel(PtDecArgs a)
     }
 }
 
-// One workgroup of 128 threads per query row: combine the partials of the chunks that hold tokens.
+// One workgroup of 128 threads per query row: combine the partials of the chunks that hold tokens.  Eight
+// chunks at a time, all their loads requested before the first is used; the running maximum is carried from
+// batch to batch (online, like the kernel above).
 __global__ __launch_bounds__(128) void merge_pt_kernel(PtDecArgs a)
 {
     const int bq = blockIdx.x, c = threadIdx.x;
     const int u = (bq / a.Hq) * a.Hkv + (bq % a.Hq) / a.rep;
+    const float *base = a.ws + (size_t)bq * a.nchunk * kPartialStride;
+    float pm[8], pl[8], po[8];
+    // (the first batch is requested before the unit's length is known: slots beyond it are ignored below)
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        const float *p = base + (size_t)min(j, a.nchunk - 1) * kPartialStride;
+        pm[j] = p[0], pl[j] = p[1], po[j] = p[4 + c];
+    }
     const int T = min(max(a.q_len[u], 0), a.Tcap);
     const int nq = (T + a.chunk - 1) / a.chunk;
-    const float *base = a.ws + (size_t)bq * a.nchunk * kPartialStride;
-    float M = -1e30f;
-    for (int ch = 0; ch < nq; ch++) M = fmaxf(M, base[(size_t)ch * kPartialStride]);
-    float L = 0.f, O = 0.f;
-    for (int ch = 0; ch < nq; ch++) {
-        const float *p = base + (size_t)ch * kPartialStride;
-        const float w = exp2f(p[0] - M);
-        L += p[1] * w;
-        O += p[4 + c] * w;
+    float M = -1e30f, L = 0.f, O = 0.f;
+    for (int c0 = 0; c0 < nq; c0 += 8) {
+        if (c0) {
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const float *p = base + (size_t)min(c0 + j, nq - 1) * kPartialStride;
+                pm[j] = p[0], pl[j] = p[1], po[j] = p[4 + c];
+            }
+        }
+        float bm = M;
+#pragma unroll
+        for (int j = 0; j < 8; j++) bm = c0 + j < nq ? fmaxf(bm, pm[j]) : bm;
+        const float sc = exp2f(M - bm);
+        L *= sc, O *= sc, M = bm;
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const bool in = c0 + j < nq;                   // (a slot beyond the unit's chunks holds anything, NaN included)
+            const float w = exp2f(pm[j] - M);
+            L = in ? __builtin_fmaf(pl[j], w, L) : L;
+            O = in ? __builtin_fmaf(po[j], w, O) : O;
+        }
     }
     a.out[(size_t)bq * kD + c] = __half_as_ushort(__float2half_rn(L > 0.f ? O / L : 0.f));
 }
@@ -423,7 +520,9 @@ static int pt_validate_cache(const minikv_pt_cache *c)
     return MINIKV_OK;
 }
 
-// token chunk of one decode workgroup: enough workgroups to cover the chip a few times over
+// token chunk of one decode workgroup: a multiple of the 256-token block, as long as the launch keeps more
+// than a thousand workgroups (a workgroup sets up the query pairs once, so chunks of several blocks pay;
+// chunks of one block measured 5-20 % slower on the batch-32 configuration)
 static int pt_chunk(const minikv_pt_shape &s)
 {
     const long units = (long)s.B * s.Hkv;
