@@ -84,6 +84,23 @@ def test_head_counts_empty_units_and_many_chunks(Hq, Hkv, B):
     assert not got.reshape(B * Hkv, Hq // Hkv, 128)[0].any()          # unit 0 holds nothing -> zeros
 
 
+@pytest.mark.parametrize("bits,G", [(2, 32), (8, 32), (2, 128), (8, 64)])
+@pytest.mark.parametrize("rep", [2, 8])
+def test_two_and_eight_heads_per_kv_head(rep, bits, G):
+    """The instantiations for 2 and for 5-8 query heads per KV head (the latter keep eight sets of sums per lane)."""
+    from oracle import ref
+    from paper_2411_18077_amd import api
+    w, inp = _inputs(1, 2 * rep, 2, 1024, seed=560 + rep + bits, ragged=True)
+    s, gc, rc = _both_caches(api, ref, w, inp, G, bits)
+    _assert_bit_exact(gc, rc)
+    out = torch.full((w.B, w.Hq, 128), float("nan"), dtype=torch.float16, device="cuda")
+    sm = 1.0 / math.sqrt(128)
+    api.minikv_decode_attn_pt(s, inp.q, gc, sm, out)
+    torch.cuda.synchronize()
+    want, _ = ref.decode_attn_pt(rc, inp.q.cpu().numpy(), sm)
+    assert np.max(np.abs(out.float().cpu().numpy() - want.astype(np.float32))) <= TOL
+
+
 def test_appending_twice_and_refused_units():
     from oracle import ref
     from paper_2411_18077_amd import api
