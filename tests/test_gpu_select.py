@@ -135,6 +135,21 @@ def test_random_shapes_and_budgets(g):
         check(g, A, n_hh.astype(np.int32), n_rw.astype(np.int32), rep=rep, idx_stride=stride)
 
 
+@pytest.mark.parametrize("U,rep,L", [(9, 4, 9000), (13, 1, 20000), (21, 2, 40000), (8, 3, 12289)])
+def test_unit_counts_that_do_not_fill_a_group_of_eight(g, U, rep, L):
+    """The several-workgroups-per-unit kernels number their workgroups in groups of eight units (one die each);
+    the last group is partly empty here.  Budgets differ from unit to unit; one unit is out of range, one keeps
+    only the window, one keeps every candidate."""
+    rng = np.random.default_rng(77 + U)
+    A = W.make_scores(U * rep, L, seed=300 + U, device="cuda", kind="attention" if U % 2 else "ties")
+    n_rw = rng.integers(0, L // 2, U)
+    n_hh = np.array([rng.integers(1, L - w) for w in n_rw])
+    n_hh[1] = L + 5                                          # out of range
+    n_hh[2] = 0                                              # window only
+    n_hh[3] = L - n_rw[3]                                    # every candidate
+    check(g, A, n_hh.astype(np.int32), n_rw.astype(np.int32), rep=rep)
+
+
 def test_empty_prompt_and_no_units(g):
     from paper_2411_18077_amd import api
     A = torch.zeros(2, 0, device="cuda")
