@@ -6,10 +6,10 @@
 //   score_key_kernel   (only when a unit has several query heads) streams the rep fp32 score rows of a
 //                      unit once, adds them in head order in fp32 and stores an order-preserving 32-bit
 //                      key per token.  Grid over (unit, 4096-token chunk): the whole chip streams.
-//   select_kernel      one workgroup of 16 waves per unit.  A radix select (11-bit digits of key - min key,
-//                      from the top bit of the keys' range down; LDS histogram, scan from the top bin
-//                      down) finds the key T of the weakest kept heavy hitter and how many tokens equal
-//                      to T are kept; then one ordered compaction
+//   select_kernel      one workgroup of 16 waves per unit.  A radix select (digits of 11, 11 and 10 bits of the
+//                      key from the top; LDS histogram, scan from the top bin down; the first digit is counted
+//                      while the keys are read from memory) finds the key T of the weakest kept heavy hitter
+//                      and how many tokens equal to T are kept; then one ordered compaction
 //                      pass writes position i if key_i > T, or key_i == T and fewer than that many equal
 //                      keys precede it, to slot (#larger before i) + min(#equal before i, kept equals).
 //                      Equal scores therefore go to the earlier position and the output is ascending
@@ -161,8 +161,37 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
         }
     };
 
-    // ---- the range [kmin, kmax] of the candidates' keys; the keys go to LDS on the way when they fit
-    uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+    // ---- radix select on the key, 11 + 11 + 10 bits from the top.  Bits hi and above of T are known (`prefix`);
+    // `rem` = how many tokens sharing them are still to be kept.  The FIRST digit is counted while the keys are
+    // read from memory (and go to LDS when they fit): that pass waits for memory, the LDS counting rides along.
+    uint32_t prefix = 0;
+    int rem = k;
+    int hi = 32;
+    // bins from the top down, two per thread; the thread whose pair crosses `rem` owns the digit
+    auto settle_digit = [&](int lo) {
+        const int c0 = hist[kSelBins - 1 - 2 * tid], c1 = hist[kSelBins - 2 - 2 * tid];
+        int incl = wave_scan_incl(c0 + c1);
+        if (lane == 63) scan_tot[wave] = incl;
+        __syncthreads();
+        {
+            const int t = lane < 16 ? scan_tot[lane] : 0;              // totals of the 16 waves, one read
+            const int ti = wave_scan_incl(t);
+            incl += __builtin_amdgcn_readlane(ti, wv) - __builtin_amdgcn_readlane(t, wv);   // waves before mine
+        }
+        const int excl = incl - c0 - c1;
+        if (excl < rem && rem <= incl) {
+            const bool upper = excl + c0 >= rem;
+            found[0] = kSelBins - 1 - 2 * tid - (upper ? 0 : 1);
+            found[1] = rem - (upper ? excl : excl + c0);
+        }
+        __syncthreads();
+        prefix |= (uint32_t)found[0] << lo;
+        rem = found[1];
+        hi = lo;
+        __syncthreads();
+    };
+    for (int b = tid; b < kSelBins; b += kSelThreads) hist[b] = 0;
+    __syncthreads();
     for (int base = 0; base < N; base += kSelThreads * kSelRangeLoads) {
         uint32_t kk[kSelRangeLoads];
         // every load of the step is issued before the first is used: indices clamped, no branches
@@ -172,33 +201,12 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
         for (int e = 0; e < kSelRangeLoads; ++e) {
             const int i = base + e * kSelThreads + tid;
             kk[e] = gkey(kk[e]);
-            kmin = min(kmin, kk[e]);
-            kmax = max(kmax, kk[e]);
             if (cached && i < N) ck[i] = kk[e];
+            hist_add(hist, i < N, (int)(kk[e] >> 21), lane);
         }
     }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, d, 64));
-        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, d, 64));
-    }
-    if (lane == 0) {
-        scan_tot[wave] = (int)kmin;
-        sub_tot[wave] = (int)kmax;
-    }
     __syncthreads();
-    for (int w = 0; w < 16; ++w) {
-        kmin = min(kmin, (uint32_t)scan_tot[w]);
-        kmax = max(kmax, (uint32_t)sub_tot[w]);
-    }
-    __syncthreads();
-
-    // ---- radix select on x = key - kmin, 11 bits at a time from the top bit of kmax - kmin down (digits of
-    // the RANGE, so that scores crowded into a few binades still spread over the histogram).  Bits hi and
-    // above of T - kmin are known (`prefix`); `rem` = how many tokens sharing them are still to be kept.
-    uint32_t prefix = 0;
-    int rem = k;
-    int hi = 32 - __clz((int)(kmax - kmin));          // 0 when all candidates are equal: T = kmin at once
+    settle_digit(21);
     while (hi > 0) {
         const int lo = max(hi - 11, 0);
         const uint32_t dm = (1u << (hi - lo)) - 1u;
@@ -223,8 +231,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
             bool match[kSelLoads], any = false;
 #pragma unroll
             for (int e = 0; e < kSelLoads; ++e) {
-                kk[e] -= kmin;
-                match[e] = tok(e) < N && (hi == 32 || (kk[e] >> hi) == (prefix >> hi));
+                match[e] = tok(e) < N && (kk[e] >> hi) == (prefix >> hi);
                 any |= match[e];
             }
             if (__ballot(any) == 0) continue;          // after the first digit few tokens still share the prefix
@@ -232,31 +239,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
             for (int e = 0; e < kSelLoads; ++e) hist_add(hist, match[e], (int)((kk[e] >> lo) & dm), lane);
         }
         __syncthreads();
-        // bins from the top down, two per thread; the thread whose pair crosses `rem` owns the digit
-        const int c0 = hist[kSelBins - 1 - 2 * tid], c1 = hist[kSelBins - 2 - 2 * tid];
-        int incl = wave_scan_incl(c0 + c1);
-        if (lane == 63) scan_tot[wave] = incl;
-        __syncthreads();
-        {
-            const int t = lane < 16 ? scan_tot[lane] : 0;              // totals of the 16 waves, one read
-            const int ti = wave_scan_incl(t);
-            incl += __builtin_amdgcn_readlane(ti, wv) - __builtin_amdgcn_readlane(t, wv);   // waves before mine
-        }
-        const int excl = incl - c0 - c1;
-        if (excl < rem && rem <= incl) {
-            const bool upper = excl + c0 >= rem;
-            found[0] = kSelBins - 1 - 2 * tid - (upper ? 0 : 1);
-            found[1] = rem - (upper ? excl : excl + c0);
-        }
-        __syncthreads();
-        prefix |= (uint32_t)found[0] << lo;
-        rem = found[1];
-        hi = lo;
-        __syncthreads();
+        settle_digit(lo);
     }
 
     // ---- ordered compaction
-    const uint32_t T = kmin + prefix;
+    const uint32_t T = prefix;
     int gt_run = 0, eq_run = 0, buf = 0;
     for (int base = 0; base < N; base += kSelThreads * 4, buf ^= 1) {
         // 4 consecutive tokens per thread: their flags are summed in the thread, one scan per wave, and the 16
