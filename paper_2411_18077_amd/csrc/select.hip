@@ -110,7 +110,9 @@ __device__ __forceinline__ void hist_add(int *hist, bool match, int d, int lane)
         atomicAdd(&hist[d], 1);
 }
 
-template <bool FROM_FLOAT>
+// FROM_FLOAT: the scores are read from A (REP rows per unit, added in head order in binary32 while they are read;
+// with REP > 1 only when the keys then stay in LDS), else the keys score_key_kernel left in `keys`.
+template <bool FROM_FLOAT, int REP = 1>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__restrict__ A,
                                                              const uint32_t *__restrict__ keys, long L,
                                                              const int *__restrict__ n_hh,
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
         for (int j = tid; j < N; j += kSelThreads) row[j] = j;
         return;
     }
-    const float *arow = A + u * L;
+    const float *arow = A + u * REP * L;
     const uint32_t *krow = keys + u * L;
     // raw 32 bits of token i, and the key they stand for
     auto gload = [&](int i) -> uint32_t { return FROM_FLOAT ? __float_as_uint(arow[i]) : krow[i]; };
@@ -192,15 +194,32 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
     };
     for (int b = tid; b < kSelBins; b += kSelThreads) hist[b] = 0;
     __syncthreads();
-    for (int base = 0; base < N; base += kSelThreads * kSelRangeLoads) {
-        uint32_t kk[kSelRangeLoads];
+    constexpr int NT = kSelRangeLoads / REP;             // tokens per thread and step: kSelRangeLoads loads in flight
+    for (int base = 0; base < N; base += kSelThreads * NT) {
+        uint32_t kk[NT];
         // every load of the step is issued before the first is used: indices clamped, no branches
+        if (REP == 1) {
 #pragma unroll
-        for (int e = 0; e < kSelRangeLoads; ++e) kk[e] = gload(min(base + e * kSelThreads + tid, N - 1));
+            for (int e = 0; e < NT; ++e) kk[e] = gload(min(base + e * kSelThreads + tid, N - 1));
 #pragma unroll
-        for (int e = 0; e < kSelRangeLoads; ++e) {
+            for (int e = 0; e < NT; ++e) kk[e] = gkey(kk[e]);
+        } else {
+            float x[NT][REP];
+#pragma unroll
+            for (int e = 0; e < NT; ++e)
+#pragma unroll
+                for (int h = 0; h < REP; ++h) x[e][h] = arow[h * L + min(base + e * kSelThreads + tid, N - 1)];
+#pragma unroll
+            for (int e = 0; e < NT; ++e) {
+                float sum = x[e][0];
+#pragma unroll
+                for (int h = 1; h < REP; ++h) sum = sum + x[e][h];                          // head order, one rounding per add
+                kk[e] = score_key(sum);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < NT; ++e) {
             const int i = base + e * kSelThreads + tid;
-            kk[e] = gkey(kk[e]);
             if (cached && i < N) ck[i] = kk[e];
             hist_add(hist, i < N, (int)(kk[e] >> 21), lane);
         }
@@ -791,7 +810,7 @@ static bool select_chunked(int32_t units, int64_t L)
     if (L <= 0 || nchunk > kChMaxChunks || ((long)units + 7) * nchunk > 0x7FFFFFFFL) return false;
     const int path = g_select_path.load();
     if (path) return path == 2;
-    return nchunk > 8 ? units <= 128 : nchunk >= 6 && units <= 96;   // (measured break-even points)
+    return nchunk > 8 && units <= 128;                  // (prompts whose keys one workgroup cannot hold in LDS; measured)
 }
 
 size_t select_workspace_bytes(int32_t units, int32_t rep, int64_t L)
@@ -841,15 +860,6 @@ int launch_select(int32_t units, int32_t rep, int64_t L, const float *A, const i
             launch_chunked_tail<false>(A, w, units, L, n_hh, n_rw, idx, idx_stride, n_tok, st);
         return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
     }
-    uint32_t *keys = (uint32_t *)workspace;
-    if (rep > 1 && L > 0) {
-        const int nchunk = (int)((L + 4095) / 4096);
-        auto k1 = rep == 2 ? score_key_kernel<2> : rep == 4 ? score_key_kernel<4> : rep == 8 ? score_key_kernel<8>
-                                                                                            : score_key_kernel<0>;
-        hipLaunchKernelGGL(k1, dim3((unsigned)((long)units * nchunk)), dim3(256), 0, st, A, keys, rep, (long)L,
-                           nchunk);
-        if (hipGetLastError() != hipSuccess) return MINIKV_ELAUNCH;
-    }
     // keys stay in LDS when the whole prompt fits beside the fixed part
     int dev = 0, max_lds = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
@@ -859,12 +869,30 @@ int launch_select(int32_t units, int32_t rep, int64_t L, const float *A, const i
     if (cap > kSelMaxCached) cap = kSelMaxCached;
     int cached = L > 0 && L <= cap;
     size_t lds = (size_t)kSelFixedWords * 4 + (cached ? (size_t)((L + 3) / 4 * 4) * 4 : 0);
-    auto kern = rep > 1 ? select_kernel<false> : select_kernel<true>;
+    // with 2, 4 or 8 heads per unit and the keys held in LDS, the select kernel adds the heads' rows itself while
+    // it reads them; otherwise (other head counts, or prompts whose keys are read again in every pass) the
+    // streaming kernel leaves the summed-score keys in the workspace first
+    const bool fused = cached && (rep == 2 || rep == 4 || rep == 8);
+    auto kern = rep == 1            ? select_kernel<true, 1>
+                : !fused            ? select_kernel<false, 1>
+                : rep == 2          ? select_kernel<true, 2>
+                : rep == 4          ? select_kernel<true, 4>
+                                    : select_kernel<true, 8>;
     if (cached && lds > 48 * 1024 &&
         hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();
         cached = 0;                                    // read the keys from memory in every pass instead
         lds = (size_t)kSelFixedWords * 4;
+        if (rep > 1) kern = select_kernel<false, 1>;
+    }
+    uint32_t *keys = (uint32_t *)workspace;
+    if (rep > 1 && L > 0 && kern == select_kernel<false, 1>) {
+        const int nchunk = (int)((L + 4095) / 4096);
+        auto k1 = rep == 2 ? score_key_kernel<2> : rep == 4 ? score_key_kernel<4> : rep == 8 ? score_key_kernel<8>
+                                                                                            : score_key_kernel<0>;
+        hipLaunchKernelGGL(k1, dim3((unsigned)((long)units * nchunk)), dim3(256), 0, st, A, keys, rep, (long)L,
+                           nchunk);
+        if (hipGetLastError() != hipSuccess) return MINIKV_ELAUNCH;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)units), dim3(kSelThreads), lds, st, A, keys, (long)L, n_hh, n_rw,
                        idx, (long)idx_stride, n_tok, cached);
