@@ -239,8 +239,10 @@ int selective_flash_attn(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, const mi
  *   idx        int32 [units][idx_stride]; n_tok int32 [units]             (device, written)
  *   workspace  device scratch of at least kv_select_workspace_bytes(units, rep, L) bytes, 16-byte aligned;
  *              contents private, no initial state required (summed-score keys when rep > 1, and per
- *              4096-token chunk a histogram, a list of threshold candidates and counts: the selection runs
- *              as three launches over (unit, chunk) so that a few long prompts still fill the chip).
+ *              4096-token chunk a histogram, a list of threshold candidates and counts: prompts of more than
+ *              32768 tokens are selected by several workgroups per unit, in launches over (unit, chunk), so
+ *              that a few long prompts still fill the chip; shorter ones by one workgroup per unit in one
+ *              or two launches -- the result is the same).
  * A unit whose budgets are out of range (negative, n_rw > L, n_hh > L - n_rw, n_hh + n_rw > idx_stride)
  * gets n_tok[u] = 0 and its idx row is left alone.  L <= 2^30. */
 size_t kv_select_workspace_bytes(int32_t units, int32_t rep, int64_t L);
