@@ -101,6 +101,43 @@ def test_two_and_eight_heads_per_kv_head(rep, bits, G):
     assert np.max(np.abs(out.float().cpu().numpy() - want.astype(np.float32))) <= TOL
 
 
+def test_benchmarked_shape_on_sampled_units():
+    """The shape bench.py times (batch 16, 32 query / 8 KV heads, 13088 of 32768 tokens kept, 4 bits, one group
+    per head): the oracle takes eight sampled units as a problem of its own (units are independent), the GPU
+    the whole batch in the launch configuration of the benchmark."""
+    from oracle import ref
+    from paper_2411_18077_amd import api
+    w = W.by_name("cfg4")
+    inp = W.make_inputs(w, "cuda", seed_offset=3)
+    n16 = (inp.n_tok // 16 * 16).to(torch.int32)
+    Tcap = (int(n16.max()) + 63) // 64 * 64
+    s = api.make_pt_shape(w.B, w.Hq, w.Hkv, 128, 128, 4, Tcap)
+    gc = api.PtCache(s)
+    api.kv_quantize_pack_pt(s, inp.K, inp.V, w.L, inp.idx, inp.idx.shape[1], n16, int(n16.max()), gc)
+    out = torch.full((w.B, w.Hq, 128), float("nan"), dtype=torch.float16, device="cuda")
+    sm = 1.0 / math.sqrt(128)
+    api.minikv_decode_attn_pt(s, inp.q, gc, sm, out)
+    torch.cuda.synchronize()
+    rep = w.Hq // w.Hkv
+    units = [0, 1, 17, 40, 63, 64, 101, w.units - 1]
+    rs = ref.RefPtShape(1, rep * len(units), len(units), 128, 128, 4, Tcap)
+    rc = ref.RefPtCache(rs)
+    sel = torch.tensor(units, device="cuda")
+    K = inp.K.view(w.units, w.L, 128)[sel].cpu().numpy()
+    V = inp.V.view(w.units, w.L, 128)[sel].cpu().numpy()
+    assert ref.quantize_pack_pt(rc, K, V, n16[sel].cpu().numpy(), inp.idx[sel].cpu().numpy()) == 0
+    q = inp.q.view(w.units, rep, 128)[sel].reshape(1, rep * len(units), 128).cpu().numpy()
+    want, _ = ref.decode_attn_pt(rc, q, sm)
+    got = out.view(w.units, rep, 128)[sel].reshape(1, rep * len(units), 128).float().cpu().numpy()
+    assert np.isfinite(out.float().cpu().numpy()).all()
+    assert np.max(np.abs(got - want.astype(np.float32))) <= TOL
+    # the packed codes and parameters of the sampled units, bit for bit
+    for name in ("Kc", "Ks", "Kz", "Vc", "Vs", "Vz"):
+        g_ = np.ascontiguousarray(gc.t[name].view(w.units, -1)[sel].cpu().numpy()).view(np.uint8)
+        r_ = np.ascontiguousarray(getattr(rc, name).reshape(len(units), -1)).view(np.uint8)
+        assert g_.shape == r_.shape and np.array_equal(g_, r_), name
+
+
 def test_appending_twice_and_refused_units():
     from oracle import ref
     from paper_2411_18077_amd import api
