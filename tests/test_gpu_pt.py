@@ -101,6 +101,31 @@ def test_two_and_eight_heads_per_kv_head(rep, bits, G):
     assert np.max(np.abs(out.float().cpu().numpy() - want.astype(np.float32))) <= TOL
 
 
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("kscale,vscale,qscale", [(40.0, 500.0, 3.0), (0.02, 3e4, 0.05), (600.0, 0.01, 60.0)])
+def test_large_and_small_magnitudes(bits, kscale, vscale, qscale):
+    """Keys, values and queries far from unit scale (up to the edge of fp16 for the values): the value-side
+    operands are fp16 (weight x V scale), so the bar is 2e-3 of the value scale."""
+    from oracle import ref
+    from paper_2411_18077_amd import api
+    w, inp = _inputs(1, 8, 2, 2048, seed=580 + bits, keep=0.5)
+    f16max = 65504.0
+    inp.K.copy_((inp.K.float() * kscale).clamp(-f16max, f16max).half())
+    inp.V.copy_((inp.V.float() * vscale).clamp(-f16max, f16max).half())
+    inp.q.copy_((inp.q.float() * qscale).clamp(-f16max, f16max).half())
+    s, gc, rc = _both_caches(api, ref, w, inp, 64, bits)
+    _assert_bit_exact(gc, rc)
+    out = torch.full((w.B, w.Hq, 128), float("nan"), dtype=torch.float16, device="cuda")
+    sm = 1.0 / math.sqrt(128)
+    api.minikv_decode_attn_pt(s, inp.q, gc, sm, out)
+    torch.cuda.synchronize()
+    want, _ = ref.decode_attn_pt(rc, inp.q.cpu().numpy(), sm)
+    got = out.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    bar = max(TOL * vscale, TOL, float(np.max(np.abs(want))) * 2.0 ** -10)     # ... or one fp16 step of the result
+    assert np.max(np.abs(got - want.astype(np.float32))) <= bar
+
+
 def test_benchmarked_shape_on_sampled_units():
     """The shape bench.py times (batch 16, 32 query / 8 KV heads, 13088 of 32768 tokens kept, 4 bits, one group
     per head): the oracle takes eight sampled units as a problem of its own (units are independent), the GPU
