@@ -82,11 +82,14 @@ __device__ inline qh2 as_qh2(uint32_t u) { return __builtin_bit_cast(qh2, u); }
 __device__ inline qh2 pk_min(qh2 a, qh2 b) { return __builtin_elementwise_min(a, b); }
 __device__ inline qh2 pk_max(qh2 a, qh2 b) { return __builtin_elementwise_max(a, b); }
 
-// code of x as a float 0..3 (round half to even, clamped): every operation a separately rounded binary32 one
-__device__ inline float quant_codef(float x, float2 zi)
+// code of x as a float 0..3 (round half to even, clamped): every operation a separately rounded binary32 one.
+// nzi = (-zero, 1/scale).  x - zero is written as the fused x * one + (-zero) with `one` a 1.0 the compiler cannot
+// see through: the conversion of the fp16 x then folds into the instruction (v_fma_mix_f32) and the result is
+// the same single rounding of x - zero.
+__device__ inline float quant_codef(_Float16 x, float2 nzi, float one)
 {
-    const float d = x - zi.x;
-    const float u = d * zi.y;
+    const float d = __builtin_fmaf((float)x, one, nzi.x);
+    const float u = d * nzi.y;
     return __builtin_amdgcn_fmed3f(rintf(u), 0.0f, 3.0f);
 }
 // Sixteen codes -> one word with code k at bit 16*(k%2) + 2*(k/2): the two half-words are summed as exact
@@ -109,10 +112,12 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
     constexpr int NPAR = (BT / G) * kD > BT * NCG ? (BT / G) * kD : BT * NCG;
 
     __shared__ __attribute__((aligned(16))) uint16_t tile[BT * kRow];
-    __shared__ __attribute__((aligned(16))) float2 par[NPAR];      // (zero, 1/scale) of every group
+    __shared__ __attribute__((aligned(16))) float2 par[NPAR];      // (-zero, 1/scale) of every group
 
     const int u = blockIdx.y;
     const int tid = threadIdx.x;
+    float one = 1.0f;
+    asm volatile("" : "+v"(one));                       // (see quant_codef)
     int q0;
     const int n = tokens_to_append<G>(a, u, q0);
     const int i0 = blockIdx.x * BT;
@@ -142,7 +147,7 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
             const size_t o = ((size_t)u * (a.Tcap / G) + (size_t)(t0 / G + g)) * kD + k_meta_pos(G, c);
             a.Ks[o] = sh;
             a.Kz[o] = zh;
-            par[g * kD + c] = float2{zf, inv};
+            par[g * kD + c] = float2{-zf, inv};
         }
     }
     __syncthreads();
@@ -167,8 +172,8 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
                 for (int k2 = 0; k2 < 4; k2++) {
                     const qh2 x = as_qh2(xw[k2]);
                     const float4 p = ps[4 * h + k2];   // (zero, inv) of channels 8h + 2k2, 8h + 2k2 + 1
-                    acc.add(8 * h + 2 * k2, quant_codef((float)x[0], float2{p.x, p.y}));
-                    acc.add(8 * h + 2 * k2 + 1, quant_codef((float)x[1], float2{p.z, p.w}));
+                    acc.add(8 * h + 2 * k2, quant_codef(x[0], float2{p.x, p.y}, one));
+                    acc.add(8 * h + 2 * k2 + 1, quant_codef(x[1], float2{p.z, p.w}, one));
                 }
             }
             Kc[k_word_index(t0 + i, w)] = acc.word();
@@ -198,7 +203,7 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
         const size_t o = ((size_t)u * a.Tcap + (size_t)(t0 + i)) * NCG + cg;
         a.Vs[o] = sh;
         a.Vz[o] = zh;
-        par[gi] = float2{zf, inv};
+        par[gi] = float2{-zf, inv};
     }
     __syncthreads();
     {
@@ -215,8 +220,8 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
             for (int p = 0; p < 16; p++) {
                 const qh2 x = as_qh2(col[p * (kRow / 2)]);
                 const float2 zi = ps[p * NCG];
-                acc0.add(p, quant_codef((float)x[0], zi));
-                acc1.add(p, quant_codef((float)x[1], zi));
+                acc0.add(p, quant_codef(x[0], zi, one));
+                acc1.add(p, quant_codef(x[1], zi, one));
             }
             Vc[v_word_index(t0 / 16 + bl, 2 * cp)] = acc0.word();
             Vc[v_word_index(t0 / 16 + bl, 2 * cp + 1)] = acc1.word();
