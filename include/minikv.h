@@ -145,6 +145,23 @@ int minikv_decode_attn(const minikv_shape *shape, const minikv_f16 *q, const min
                        float sm_scale, minikv_f16 *out, void *workspace, size_t workspace_bytes,
                        void *stream);
 
+/* The decode step in ONE launch, for callers that run kv_append_residual and minikv_decode_attn back to back (a
+ * launch costs microseconds on this hardware however little it does): Algorithm 1 lines 9 and 17-19 together.
+ * Equivalent to kv_append_residual(shape, k_new, v_new, cache) followed by minikv_decode_attn(...), same output
+ * bit for bit, except for where the new residual lengths go:
+ *   k_new, v_new  fp16 [B*Hkv][128], 16-byte aligned                       (device, read)
+ *   r_len_next    int32 [B*Hkv], NOT cache->r_len                          (device, written)
+ * Every wave of the launch reads cache->r_len when it starts, so the lengths after the append cannot go to the
+ * same array: r_len_next[u] receives r_len[u] + 1 (r_len[u] unchanged when the buffer is full or the value is
+ * out of range, as kv_append_residual leaves it), the new rows are written to their place in cache->Rk, Rv, and
+ * the caller then uses r_len_next as the cache's r_len (swap the two pointers from step to step; no
+ * synchronisation is involved).  kv_flush_residual and every other call take whichever array is current.
+ * Other arguments, checks and status codes as minikv_decode_attn; MINIKV_EINVAL when r_len_next is null,
+ * misaligned or equal to cache->r_len. */
+int minikv_decode_step(const minikv_shape *shape, const minikv_f16 *q, const minikv_f16 *k_new, const minikv_f16 *v_new,
+                       const minikv_cache *cache, int32_t *r_len_next, float sm_scale, minikv_f16 *out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
 /* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc): minikv_decode_attn with the split-K workspace held in a
  * device array of the library itself.  Same arguments, same kernel and same result as minikv_decode_attn

@@ -80,6 +80,9 @@ def lib():
         l.minikv_decode_attn.restype = C.c_int
         l.minikv_decode_attn.argtypes = [C.POINTER(MinikvShape), P, C.POINTER(MinikvCache), C.c_float, P, P,
                                          C.c_size_t, P]
+        l.minikv_decode_step.restype = C.c_int
+        l.minikv_decode_step.argtypes = [C.POINTER(MinikvShape), P, P, P, C.POINTER(MinikvCache), P, C.c_float, P, P,
+                                         C.c_size_t, P]
         l.minikv_decode_attn_static.restype = C.c_int
         l.minikv_decode_attn_static.argtypes = [C.POINTER(MinikvShape), P, C.POINTER(MinikvCache), C.c_float, P, P]
         l.minikv_static_workspace_units.restype = C.c_size_t
@@ -169,6 +172,12 @@ class Cache:
     def nbytes(self):
         return sum(v.numel() * v.element_size() for v in self.t.values())
 
+    def swap_r_len(self, other):
+        """After minikv_decode_step: `other` (the array it wrote) becomes the cache's r_len; returns the old one."""
+        old = self.t["r_len"]
+        self.t["r_len"] = other
+        return old
+
 
 def kv_quantize_pack(shape, K, V, L, idx, idx_stride, n_tok, max_tok, cache, stream=None):
     cc = cache.c()
@@ -237,6 +246,16 @@ def minikv_diag_redo_count(shape, workspace):
     n = C.c_int32(0)
     _check(lib().minikv_diag_redo_count(C.byref(shape), _ptr(workspace), C.byref(n)), "minikv_diag_redo_count")
     return int(n.value)
+
+
+def minikv_decode_step(shape, q, k_new, v_new, cache, r_len_next, sm_scale, out, stream=None):
+    """Append + attend in one launch; afterwards r_len_next holds the residual lengths (the caller swaps it with
+    cache.r_len: see Cache.swap_r_len)."""
+    cc = cache.c()
+    _check(lib().minikv_decode_step(C.byref(shape), _ptr(q), _ptr(k_new), _ptr(v_new), C.byref(cc), _ptr(r_len_next),
+                                    float(sm_scale), _ptr(out), _ptr(cache.workspace),
+                                    cache.workspace.numel() * cache.workspace.element_size(), _stream(stream)),
+           "minikv_decode_step")
 
 
 def minikv_diag_select_path(path):

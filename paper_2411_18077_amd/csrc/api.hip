@@ -169,6 +169,23 @@ int minikv_decode_attn(const minikv_shape *s, const minikv_f16 *q, const minikv_
     return launch_decode(*s, q, *c, sm_scale, out, workspace, g_variant.load(), (hipStream_t)stream);
 }
 
+int minikv_decode_step(const minikv_shape *s, const minikv_f16 *q, const minikv_f16 *k_new, const minikv_f16 *v_new,
+                       const minikv_cache *c, int32_t *r_len_next, float sm_scale, minikv_f16 *out, void *workspace,
+                       size_t workspace_bytes, void *stream)
+{
+    int rc = validate_shape(s);
+    if (rc) return rc;
+    if ((rc = validate_cache(*s, c))) return rc;
+    if (!aligned16(q) || !aligned16(out) || !aligned16(workspace) || !aligned16(k_new) || !aligned16(v_new))
+        return MINIKV_EINVAL;
+    if (!k_new || !v_new || !r_len_next || ((uintptr_t)r_len_next & 3u) || r_len_next == c->r_len) return MINIKV_EINVAL;
+    if (!(sm_scale == sm_scale) || sm_scale - sm_scale != 0.0f) return MINIKV_EINVAL;   // NaN / Inf
+    if (workspace_bytes < minikv_workspace_bytes(s)) return MINIKV_EWORKSPACE;
+    AppendArgs ap;
+    ap.k_new = k_new, ap.v_new = v_new, ap.r_len_out = r_len_next;
+    return launch_decode(*s, q, *c, sm_scale, out, workspace, 0, (hipStream_t)stream, &ap);
+}
+
 size_t selective_flash_attn_workspace_bytes(int32_t B, int32_t Hkv, int64_t L)
 {
     if (B <= 0 || Hkv <= 0 || L < 1) return 0;

@@ -76,13 +76,19 @@ int launch_quantize(const minikv_shape &s, const minikv_f16 *K, const minikv_f16
                     const minikv_cache &c, bool flush, hipStream_t st);
 int launch_append(const minikv_shape &s, const minikv_f16 *k_new, const minikv_f16 *v_new,
                   const minikv_cache &c, hipStream_t st);
+// the new token's rows and where the lengths after the append go: all null for plain attention
+struct AppendArgs {
+    const minikv_f16 *k_new = nullptr, *v_new = nullptr;
+    int32_t *r_len_out = nullptr;
+};
 int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
-                  minikv_f16 *out, void *workspace, int variant, hipStream_t st);
+                  minikv_f16 *out, void *workspace, int variant, hipStream_t st, const AppendArgs *ap = nullptr);
 
 // the same with the three parts of the workspace given one by one: per-unit ticket counters (ws_units ints),
 // sub-group ticket counters (2 * ws_units + kMaxStreamWaves ints), the redo counter (one int), split-K partials
 int launch_decode_parts(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
-                        minikv_f16 *out, int *cnt, int *cnt1, int *redo, float *partials, int variant, hipStream_t st);
+                        minikv_f16 *out, int *cnt, int *cnt1, int *redo, float *partials, int variant, hipStream_t st,
+                        const AppendArgs &ap = AppendArgs());
 int validate_cache(const minikv_shape &s, const minikv_cache *c);
 bool aligned16(const void *p);
 

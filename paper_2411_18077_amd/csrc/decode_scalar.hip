@@ -189,22 +189,25 @@ int launch_decode_scalar(const DecArgs &a, int G, int units, hipStream_t st)
 }
 
 int launch_decode(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
-                  minikv_f16 *out, void *workspace, int variant, hipStream_t st)
+                  minikv_f16 *out, void *workspace, int variant, hipStream_t st, const AppendArgs *ap)
 {
     int *cnt = reinterpret_cast<int *>(workspace);
     return launch_decode_parts(s, q, c, sm_scale, out, cnt, cnt + ws_units(s), cnt + 3 * ws_units(s) + kMaxStreamWaves,
                                reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + ws_counter_bytes(s)),
-                               variant, st);
+                               variant, st, ap ? *ap : AppendArgs());
 }
 
 int launch_decode_parts(const minikv_shape &s, const minikv_f16 *q, const minikv_cache &c, float sm_scale,
-                        minikv_f16 *out, int *cnt, int *cnt1, int *redo, float *partials, int variant, hipStream_t st)
+                        minikv_f16 *out, int *cnt, int *cnt1, int *redo, float *partials, int variant, hipStream_t st,
+                        const AppendArgs &ap)
 {
     const DecodeGeom g = decode_geom(s);
     DecArgs a;
     a.q = q; a.Kc = c.Kc; a.Vc = c.Vc; a.Ks = c.Ks; a.Kz = c.Kz; a.Vs = c.Vs; a.Vz = c.Vz;
     a.Rk = c.Rk; a.Rv = c.Rv; a.q_len = c.q_len; a.r_len = c.r_len;
     a.out = out;
+    a.append = ap.k_new != nullptr;
+    a.k_new = ap.k_new; a.v_new = ap.v_new; a.Rk_w = c.Rk; a.Rv_w = c.Rv; a.r_len_out = ap.r_len_out;
     a.first_slot = 0;
     a.cnt = cnt;
     a.cnt1 = cnt1;
@@ -219,6 +222,7 @@ int launch_decode_parts(const minikv_shape &s, const minikv_f16 *q, const minikv
     fast_div_setup((uint32_t)s.Hkv, a.hkv_magic, a.hkv_shift);
     int rc;
     if (variant == 0) variant = 3;                     // default variant
+    if (a.append && variant != 3) return MINIKV_EUNSUPPORTED;   // the fused step exists in the default kernel only
     if (variant == 1) rc = launch_decode_scalar(a, s.G, units, st);
     else return launch_decode_tiled(a, s.G, units, variant, st);      // merges in the same launch
     if (rc) return rc;

@@ -50,16 +50,37 @@ namespace minikv {
 // its unit (device-scope ticket counter) merges the unit's partials and writes the fp16 output, so one
 // kernel launch does the whole call.  (Drawing passes from a per-unit counter instead was tried: a vector
 // atomic per pass, even one whose result is needed a full pass later, slowed the pass loop by 40 %.)
-struct UnitItems { int nq, nr, T, R; };
+struct UnitItems { int nq, nr, T, R, rn; };   // rn: residual row the fused step appends (-1: none)
 constexpr int kSkew16 = 10;             // share (in sixteenths) of a wave pair's range given to its first wave
 constexpr int kWQ = 2, kWR = 7;        // relative cost of a quantized pass (128 tokens, 12 KB) and a residual
                                        // item (64 fp16 tokens, 32 KB), measured
 
-__device__ inline UnitItems unit_items(const DecArgs &a, int up)
+// Residual tokens a unit attends to: its stored ones, plus -- in the fused step -- the token this launch appends
+// (when the buffer has room for it, as kv_append_residual would).
+// A 32-bit word that no kernel of this launch writes, read through the constant address space: a wave-uniform
+// address then gets a scalar load, which does not queue behind the wave's outstanding vector loads.  (Without
+// this the fused step's stores of 32-bit words make the compiler read the lengths with vector loads.)
+__device__ inline int load_const_i32(const int32_t *p)
+{
+    typedef const __attribute__((address_space(4))) int32_t *const_ptr;
+    return *(const_ptr)(uintptr_t)p;
+}
+// (bit kAppBit of the result says that a token is appended, so that one register carries both facts)
+constexpr int kAppBit = 20;
+__device__ inline int res_len(bool APPEND, const DecArgs &a, int r)
+{
+    const int rc = clampi(r, 0, a.Rcap);
+    return APPEND && r >= 0 && r < a.Rcap ? (rc + 1) | (1 << kAppBit) : rc;
+}
+__device__ inline UnitItems make_items(bool APPEND, int T, int Rtag)
+{
+    const int R = APPEND ? Rtag & ((1 << kAppBit) - 1) : Rtag;
+    return UnitItems{(T + kPass - 1) / kPass, (R + 63) / 64, T, R, APPEND && (Rtag >> kAppBit) ? R - 1 : -1};
+}
+__device__ inline UnitItems unit_items(bool APPEND, const DecArgs &a, int up)
 {
     const int u = up >> a.hs_shift;
-    const int T = clampi(a.q_len[u], 0, a.Tcap), R = clampi(a.r_len[u], 0, a.Rcap);
-    return UnitItems{(T + kPass - 1) / kPass, (R + 63) / 64, T, R};
+    return make_items(APPEND, clampi(load_const_i32(a.q_len + u), 0, a.Tcap), res_len(APPEND, a, load_const_i32(a.r_len + u)));
 }
 // P weight units are cut into NW = 2^nw_log ranges.  Waves 2p and 2p+1 share the pair range
 // [p*2P >> nw_log, (p+1)*2P >> nw_log); the first of them takes skew16/16 of it (8 = equal halves).
@@ -108,9 +129,15 @@ __device__ inline float *slot_ptr(const DecArgs &a, int slot, int h)
 // PAIRED (units with at most two query heads, i.e. multi-head attention): the four rows of the K-phase
 // A operand are (head 0 hi, head 0 lo, head 1 hi, head 1 lo) instead of four heads, so one matrix
 // instruction does the work of the hi and the lo one, and the two result rows of a head are added afterwards.
-template <int G, bool LO, bool PAIRED>
+//
+// FUSED: the instance that serves the fused decode step (the plain call compiles none of it).  Inside it the
+// step's code still hangs on the run-time flag a.append and not on the template parameter: measured on the
+// 16 x 32768 workload, the instance built with the flag as a constant ran 3 us (7 %) slower, with or without a
+// token to append -- the compiler then arranges the unit set-up and the residual item differently.
+template <int G, bool LO, bool PAIRED, bool FUSED>
 __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecArgs a)
 {
+    const bool APPEND = FUSED && a.append;
     static_assert(!PAIRED || LO, "the paired rows are the hi and lo parts");
     constexpr int NHQ = PAIRED ? 2 : kNH;                  // heads the quantized passes work on
     // K side: a K group spans G/2 token-lanes = BGK blocks of 4 lanes.  Block j of a group supplies the
@@ -140,6 +167,7 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
         const int bq0 = bi * a.Hq + (u - bi * a.Hkv) * a.rep + hs * kNH;
         const int nh = min(kNH, a.rep - hs * kNH);
         for (int i = lane; i < nh * kD; i += 64) a.out[(size_t)bq0 * kD + i] = 0;   // the whole wave
+        if (APPEND && lane == 0 && hs == 0) a.r_len_out[u] = a.r_len[u];          // (nothing was appended: see res_len)
     };
     // lengths of units base + 64k + lane, k = 0..3: all eight loads go out before any is waited for
     auto lengths4 = [&](int base, int (&T)[4], int (&R)[4]) {
@@ -155,14 +183,32 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
         for (int k = 0; k < 4; k++) {
             const bool in = base + 64 * k + lane < NU;
             T[k] = in ? clampi(t[k], 0, a.Tcap) : 0;
-            R[k] = in ? clampi(r[k], 0, a.Rcap) : 0;
+            R[k] = in ? res_len(APPEND, a, r[k]) : 0;
         }
     };
-    auto weight_of = [&](int T, int R) -> int { return kWQ * ((T + kPass - 1) / kPass) + kWR * ((R + 63) >> 6); };
+    auto weight_of = [&](int T, int R) -> int {
+        if (APPEND) R &= (1 << kAppBit) - 1;
+        return kWQ * ((T + kPass - 1) / kPass) + kWR * ((R + 63) >> 6);
+    };
     const bool small = NU <= 256;
     int Tl[4], Rl[4], wl4[4], incl4[4];
     int P = 0;
     bool empties = false;                                  // some unit of this wave's share holds no token
+    // Fused step: workgroup b files the new rows of units b, b + grid size, ... in the residual buffer (32 lanes,
+    // 16 bytes each: the key row, then the value row).  Nothing in this launch reads those rows from the buffer
+    // -- the residual items take them from the caller's arrays -- so the copy needs no ordering against the
+    // rest; the first unit's rows are requested here and stored after the lengths below have arrived, so that
+    // the wave waits once for both.  (Inside the residual item the copy cost the whole launch 4 us: whatever
+    // form it took there, the item's local-memory reads and its loads lost their overlap.)
+    uint4 new_piece = {0u, 0u, 0u, 0u};
+    int new_row = -1;
+    const bool files_new = APPEND && (int)blockIdx.x < a.units && lane < 32;
+    auto new_src = [&](int u) { return reinterpret_cast<const uint4 *>((lane < 16 ? a.k_new : a.v_new) + (size_t)u * kD) + (lane & 15); };
+    auto new_dst = [&](int u, int r) { return reinterpret_cast<uint4 *>((lane < 16 ? a.Rk_w : a.Rv_w) + ((size_t)u * a.Rcap + r) * kD) + (lane & 15); };
+    if (files_new) {
+        new_row = a.r_len[blockIdx.x];
+        new_piece = *new_src(blockIdx.x);
+    }
     for (int base = 0; base < NU; base += 256) {
         lengths4(base, Tl, Rl);
 #pragma unroll
@@ -174,9 +220,16 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             P += __builtin_amdgcn_readlane(incl4[k], 63);
         }
     }
+    if (files_new) {
+        if (new_row >= 0 && new_row < a.Rcap) *new_dst(blockIdx.x, new_row) = new_piece;
+        for (int u = blockIdx.x + gridDim.x; u < a.units; u += gridDim.x) {     // (more units than workgroups)
+            const int r = a.r_len[u];
+            if (r >= 0 && r < a.Rcap) *new_dst(u, r) = *new_src(u);
+        }
+    }
     if (__ballot(empties)) {                               // rare: look again, one unit at a time
         for (int uu = blockIdx.x; uu < NU; uu += gridDim.x) {
-            const UnitItems it = unit_items(a, uu);
+            const UnitItems it = unit_items(APPEND, a, uu);
             if (it.nq + it.nr == 0) zero_fill(uu);
         }
     }
@@ -250,8 +303,7 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
     // A wave owns the items whose start position lies in [start, end).
     for (; up < NU && ib < end; up++) {
         // (the lengths of the first unit are already known)
-        const UnitItems it = up == up_first ? UnitItems{(T_first + kPass - 1) / kPass, (R_first + 63) / 64, T_first, R_first}
-                                            : unit_items(a, up);
+        const UnitItems it = up == up_first ? make_items(APPEND, T_first, R_first) : unit_items(APPEND, a, up);
         const int wt = kWR * it.nr + kWQ * it.nq;
         if (wt == 0) continue;
         const long ib_next = ib + wt;
@@ -405,11 +457,17 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             const int t0 = ri * 64;
             const bool valid = t0 + lane < R;
 
+            // (fused step: the unit's last residual row is the token this launch appends; it is read from the
+            // caller's new rows, never from the residual buffer, where another wave files it at some point of
+            // this launch)
+            const int r_new = it.rn;                       // (a full or invalid buffer takes no token)
+            const uint16_t *kn = APPEND ? a.k_new + (size_t)u * kD : nullptr, *vn = APPEND ? a.v_new + (size_t)u * kD : nullptr;
             Words<64> g;
 #pragma unroll
             for (int i = 0; i < 16; i++) {
                 const int rr = t0 + 4 * i + rsub;
-                const uint4 x = reinterpret_cast<const uint4 *>(Rk + (size_t)(rr < R ? rr : 0) * kD)[piece];
+                const uint16_t *src = rr == r_new ? kn : Rk + (size_t)(rr < R ? rr : 0) * kD;
+                const uint4 x = reinterpret_cast<const uint4 *>(src)[piece];
                 g.v[4 * i] = x.x; g.v[4 * i + 1] = x.y; g.v[4 * i + 2] = x.z; g.v[4 * i + 3] = x.w;
             }
             // A operands of the scores: block b supplies k-steps b and b+16 (channels 4b.., 64+4b..) of head `row`
@@ -429,7 +487,8 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
 #pragma unroll
             for (int i = 0; i < 16; i++) {
                 const int rr = t0 + 4 * i + rsub;
-                const uint4 x = reinterpret_cast<const uint4 *>(Rv + (size_t)(rr < R ? rr : 0) * kD)[piece];
+                const uint16_t *src = rr == r_new ? vn : Rv + (size_t)(rr < R ? rr : 0) * kD;
+                const uint4 x = reinterpret_cast<const uint4 *>(src)[piece];
                 g.v[4 * i] = x.x; g.v[4 * i + 1] = x.y; g.v[4 * i + 2] = x.z; g.v[4 * i + 3] = x.w;
             }
             __builtin_amdgcn_wave_barrier();
@@ -755,8 +814,15 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
         // =============================== publish this wave's partial of the unit
         int lane_p = lane;
         asm volatile("" : "+v"(lane_p));                   // (opaque copy: address terms computed here, not hoisted)
+        // (fused step: the unit's residual length after the append, for the next call -- into an array of its own,
+        // because every wave of THIS launch still reads the old lengths when it starts; written by the wave that
+        // writes the unit's output)
+        auto write_next_len = [&]() {
+            if (APPEND && lane == 0) a.r_len_out[u] = it.rn >= 0 ? it.rn + 1 : a.r_len[u];
+        };
         if (expected == 1) {
             // the only partial of its unit: normalise and write the result directly
+            write_next_len();
 #pragma unroll
             for (int h = 0; h < kNH; h++) {
                 if (h < nheads) {
@@ -833,6 +899,7 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                 }
             };
             auto write_out = [&]() {
+                write_next_len();
 #pragma unroll
                 for (int h = 0; h < kNH; h++) {
                     if (h >= nheads) continue;
@@ -890,14 +957,14 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
     }
 }
 
-template <int G, bool LO, bool PAIRED>
+template <int G, bool LO, bool PAIRED, bool APPEND>
 static int launch_stream(DecArgs a, hipStream_t st)
 {
     constexpr int NCG = kD / G;
     constexpr size_t q_bytes = (size_t)NCG * kPsG * 2;
     constexpr size_t r_bytes = (size_t)kNH * kD * 2 + (size_t)64 * kKRowH * 2;
     constexpr size_t lds_bytes = q_bytes > r_bytes ? q_bytes : r_bytes;
-    auto kern = decode_stream_kernel<G, LO, PAIRED>;
+    auto kern = decode_stream_kernel<G, LO, PAIRED, APPEND>;
     static int resident = 0;                               // single-wave workgroups the device holds at once
     if (resident == 0) {
         int dev = 0, cus = 0, per_cu = 0;
@@ -921,11 +988,20 @@ static int launch_stream(DecArgs a, hipStream_t st)
 template <bool LO, bool PAIRED>
 static int launch_stream_g(const DecArgs &a, int G, hipStream_t st)
 {
+    if (a.append) {
+        switch (G) {
+        case 16: return launch_stream<16, LO, PAIRED, true>(a, st);
+        case 32: return launch_stream<32, LO, PAIRED, true>(a, st);
+        case 64: return launch_stream<64, LO, PAIRED, true>(a, st);
+        case 128: return launch_stream<128, LO, PAIRED, true>(a, st);
+        }
+        return MINIKV_EUNSUPPORTED;
+    }
     switch (G) {
-    case 16: return launch_stream<16, LO, PAIRED>(a, st);
-    case 32: return launch_stream<32, LO, PAIRED>(a, st);
-    case 64: return launch_stream<64, LO, PAIRED>(a, st);
-    case 128: return launch_stream<128, LO, PAIRED>(a, st);
+    case 16: return launch_stream<16, LO, PAIRED, false>(a, st);
+    case 32: return launch_stream<32, LO, PAIRED, false>(a, st);
+    case 64: return launch_stream<64, LO, PAIRED, false>(a, st);
+    case 128: return launch_stream<128, LO, PAIRED, false>(a, st);
     }
     return MINIKV_EUNSUPPORTED;
 }
