@@ -22,6 +22,12 @@ int minikv_stream_read_probe(const void *src, size_t bytes, uint32_t *sums, void
  * the fast range.  Synchronous (a blocking 4-byte copy to the host); count is a HOST pointer. */
 int minikv_diag_redo_count(const minikv_shape *shape, const void *workspace, int32_t *count);
 
+/* How minikv_decode_attn / minikv_decode_step cut the work into waves (process-wide): 0 = chosen by shape
+ * (default), 1 = a residual item of 64 tokens weighs 3.5 quantized passes of 128, as measured (what large launches
+ * use), 2 = every item weighs the same (what launches of few items use, so that every item gets a wave).  Both
+ * give the same result up to the order of the merge; the parity tests run each.  MINIKV_EINVAL otherwise. */
+int         minikv_diag_decode_weights(int mode);
+
 /* Which kernels kv_select_hh_rw launches (process-wide): 0 = chosen by shape (default), 1 = always one workgroup
  * per unit, 2 = several workgroups per unit whenever the prompt has at most 1024 chunks of 4096 tokens.  Both
  * give the same positions; the parity tests run each.  MINIKV_EINVAL for any other value. */

@@ -61,6 +61,8 @@ def lib():
         l.minikv_strvariant.argtypes = [C.c_int]
         l.minikv_set_variant.restype = C.c_int
         l.minikv_set_variant.argtypes = [C.c_int]
+        l.minikv_diag_decode_weights.restype = C.c_int
+        l.minikv_diag_decode_weights.argtypes = [C.c_int]
         l.minikv_diag_select_path.restype = C.c_int
         l.minikv_diag_select_path.argtypes = [C.c_int]
         l.minikv_buffer_bytes.restype = C.c_size_t
@@ -256,6 +258,10 @@ def minikv_decode_step(shape, q, k_new, v_new, cache, r_len_next, sm_scale, out,
                                     float(sm_scale), _ptr(out), _ptr(cache.workspace),
                                     cache.workspace.numel() * cache.workspace.element_size(), _stream(stream)),
            "minikv_decode_step")
+
+
+def minikv_diag_decode_weights(mode):
+    _check(lib().minikv_diag_decode_weights(int(mode)), "minikv_diag_decode_weights")
 
 
 def minikv_diag_select_path(path):

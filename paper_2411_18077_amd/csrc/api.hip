@@ -254,6 +254,11 @@ int minikv_diag_redo_count(const minikv_shape *s, const void *workspace, int32_t
     return hipMemcpy(count, p, sizeof(int32_t), hipMemcpyDeviceToHost) == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
 }
 
+int minikv_diag_decode_weights(int mode)
+{
+    return set_decode_weights(mode) ? MINIKV_OK : MINIKV_EINVAL;
+}
+
 int minikv_diag_select_path(int path)
 {
     return set_select_path(path) ? MINIKV_OK : MINIKV_EINVAL;

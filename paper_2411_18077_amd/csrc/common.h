@@ -96,6 +96,7 @@ int launch_prefill(int32_t B, int32_t Hq, int32_t Hkv, int64_t L, const minikv_f
                    const minikv_f16 *V, float sm_scale, minikv_f16 *XO, float *lse, float *A_cumul,
                    void *workspace, hipStream_t st);
 size_t select_workspace_bytes(int32_t units, int32_t rep, int64_t L);
+bool set_decode_weights(int mode); // 0 = by shape, 1 = measured item weights, 2 = unit weights
 bool set_select_path(int path);   // 0 = by shape, 1 = one workgroup per unit, 2 = several (when the prompt allows)
 int launch_select(int32_t units, int32_t rep, int64_t L, const float *A, const int32_t *n_hh,
                   const int32_t *n_rw, int32_t *idx, int64_t idx_stride, int32_t *n_tok, void *workspace,

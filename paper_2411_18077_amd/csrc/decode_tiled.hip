@@ -35,6 +35,8 @@
 // Input domain: every finite fp16 input.  The fp16 operands of the matrix instructions hold |q * Ks| < 65504
 // and V scales < 4096 with the default scalings; a wave whose sums show an overflow repeats its share of the
 // unit with range-normalised operands (see "Operand ranges" in the kernel).
+#include <atomic>
+
 #include "decode_wave.h"
 
 namespace minikv {
@@ -52,7 +54,7 @@ namespace minikv {
 // atomic per pass, even one whose result is needed a full pass later, slowed the pass loop by 40 %.)
 struct UnitItems { int nq, nr, T, R, rn; };   // rn: residual row the fused step appends (-1: none)
 constexpr int kSkew16 = 10;             // share (in sixteenths) of a wave pair's range given to its first wave
-constexpr int kWQ = 2, kWR = 7;        // relative cost of a quantized pass (128 tokens, 12 KB) and a residual
+constexpr int kPassWeight = 2, kResidualWeight = 7;   // relative cost of a quantized pass (128 tokens, 12 KB) and a residual
                                        // item (64 fp16 tokens, 32 KB), measured
 
 // Residual tokens a unit attends to: its stored ones, plus -- in the fused step -- the token this launch appends
@@ -134,9 +136,16 @@ __device__ inline float *slot_ptr(const DecArgs &a, int slot, int h)
 // step's code still hangs on the run-time flag a.append and not on the template parameter: measured on the
 // 16 x 32768 workload, the instance built with the flag as a constant ran 3 us (7 %) slower, with or without a
 // token to append -- the compiler then arranges the unit set-up and the residual item differently.
-template <int G, bool LO, bool PAIRED, bool FUSED>
+//
+// FLAT: every item weighs 1.  A range of the work line must be at least one residual item long, so with the
+// measured weights a small workload is cut into few ranges -- one sequence of 1024 tokens and 8 heads gets 16
+// waves of 4 to 6 items each, 16 us of which 7 are items worked off one after the other.  When the whole
+// launch cannot hold more items than half the waves the device holds, balance does not matter and
+// parallelism does: with unit weights every item gets a wave of its own.
+template <int G, bool LO, bool PAIRED, bool FUSED, bool FLAT>
 __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecArgs a)
 {
+    constexpr int kWQ = FLAT ? 1 : kPassWeight, kWR = FLAT ? 1 : kResidualWeight;
     const bool APPEND = FUSED && a.append;
     static_assert(!PAIRED || LO, "the paired rows are the hi and lo parts");
     constexpr int NHQ = PAIRED ? 2 : kNH;                  // heads the quantized passes work on
@@ -957,6 +966,23 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
     }
 }
 
+template <int G, bool LO, bool PAIRED, bool APPEND, bool FLAT>
+static int launch_stream_w(DecArgs a, long nw, int resident, size_t lds_bytes, hipStream_t st)
+{
+    a.first_slot = resident / 2;
+    a.skew16 = kSkew16;
+    hipLaunchKernelGGL((decode_stream_kernel<G, LO, PAIRED, APPEND, FLAT>), dim3((unsigned)nw), dim3(64), lds_bytes, st, a);
+    return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
+}
+
+static std::atomic<int> g_decode_weights{0};
+bool set_decode_weights(int mode)
+{
+    if (mode < 0 || mode > 2) return false;
+    g_decode_weights.store(mode);
+    return true;
+}
+
 template <int G, bool LO, bool PAIRED, bool APPEND>
 static int launch_stream(DecArgs a, hipStream_t st)
 {
@@ -964,7 +990,7 @@ static int launch_stream(DecArgs a, hipStream_t st)
     constexpr size_t q_bytes = (size_t)NCG * kPsG * 2;
     constexpr size_t r_bytes = (size_t)kNH * kD * 2 + (size_t)64 * kKRowH * 2;
     constexpr size_t lds_bytes = q_bytes > r_bytes ? q_bytes : r_bytes;
-    auto kern = decode_stream_kernel<G, LO, PAIRED, APPEND>;
+    auto kern = decode_stream_kernel<G, LO, PAIRED, APPEND, false>;
     static int resident = 0;                               // single-wave workgroups the device holds at once
     if (resident == 0) {
         int dev = 0, cus = 0, per_cu = 0;
@@ -979,10 +1005,12 @@ static int launch_stream(DecArgs a, hipStream_t st)
     long nw = resident < kMaxStreamWaves ? resident : kMaxStreamWaves;
     if (nw > cap_items) nw = cap_items;
     if (nw < 1) nw = 1;
-    a.first_slot = resident / 2;
-    a.skew16 = kSkew16;
-    hipLaunchKernelGGL(kern, dim3((unsigned)nw), dim3(64), lds_bytes, st, a);
-    return hipGetLastError() == hipSuccess ? MINIKV_OK : MINIKV_ELAUNCH;
+    // (unit weights when the launch cannot hold more items than half the waves the device holds: measured on
+    // shapes of 80 to 2240 items, they win up to 608 items -- 13.3 against 16.7 us -- tie at 560 and lose from
+    // 1120 on -- 19.8 against 17.7 us)
+    const int mode = g_decode_weights.load();
+    return (mode == 0 ? cap_items * 2 <= (long)resident : mode == 2) ? launch_stream_w<G, LO, PAIRED, APPEND, true>(a, nw, resident, lds_bytes, st)
+                                 : launch_stream_w<G, LO, PAIRED, APPEND, false>(a, nw, resident, lds_bytes, st);
 }
 
 template <bool LO, bool PAIRED>

@@ -25,7 +25,7 @@ def test_exports_every_declared_symbol(api):
     names = sorted(set(names))
     assert {"kv_quantize_pack", "kv_append_residual", "kv_flush_residual", "minikv_decode_attn",
             "minikv_workspace_bytes", "minikv_buffer_bytes", "minikv_cache_bytes", "minikv_abi_version", "kv_select_hh_rw",
-            "minikv_set_variant", "minikv_stream_read_probe", "minikv_diag_redo_count",
+            "minikv_set_variant", "minikv_stream_read_probe", "minikv_diag_redo_count", "minikv_diag_decode_weights",
             "kv_select_workspace_bytes", "kv_pyramid_budget", "selective_flash_attn",
             "selective_flash_attn_workspace_bytes"} <= set(names)
     l = api.lib()
@@ -80,6 +80,8 @@ def test_pointer_and_workspace_checks(api):
     assert l.kv_quantize_pack(C.byref(s), P(0x1000), P(0x1000), 64, None, 0, P(0x1000), 0, C.byref(good), None) == 0
     assert l.minikv_set_variant(99) == -1 and l.minikv_set_variant(2) == -1 and l.minikv_set_variant(4) == -1
     assert l.minikv_set_variant(0) == 0
+    assert l.minikv_diag_decode_weights(3) == -1 and l.minikv_diag_decode_weights(-1) == -1
+    assert l.minikv_diag_decode_weights(2) == 0 and l.minikv_diag_decode_weights(0) == 0
     assert b"workspace" in l.minikv_strerror(-3)
 
 

@@ -11,7 +11,10 @@ TOL = 2e-3
 
 import os
 
-VARIANTS = [int(v) for v in os.environ.get("MINIKV_TEST_VARIANTS", "1,3").split(",")]
+# 1 = the plain scalar-loop kernel, 3 = the product kernel; 31 / 32 = the product kernel with its work cut by
+# measured / by unit item weights whatever the shape (by itself it picks by the number of items)
+VARIANTS = [pytest.param(int(v), id={31: "3-measured-weights", 32: "3-unit-weights"}.get(int(v), v))
+            for v in os.environ.get("MINIKV_TEST_VARIANTS", "1,3,31,32").split(",")]
 
 
 @pytest.fixture(scope="module")
@@ -36,12 +39,14 @@ def run_both(g, w, r_len, variant, Tcap=None, seed_offset=0, mutate=None, sm=Non
         prepare(inp, rc)
     sm = g.sm_scale() if sm is None else sm
     out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=torch.float16, device="cuda")
-    api.minikv_set_variant(variant)
+    api.minikv_set_variant(3 if variant > 10 else variant)
+    api.minikv_diag_decode_weights(variant - 30 if variant > 10 else 0)
     try:
         api.minikv_decode_attn(s, inp.q, gc, sm, out)
         torch.cuda.synchronize()
     finally:
         api.minikv_set_variant(0)
+        api.minikv_diag_decode_weights(0)
     want, _, _ = ref.decode_attn(rc, g.to_np(inp.q), sm)
     got = g.to_np(out).astype(np.float64)
     assert np.isfinite(got).all()
