@@ -24,6 +24,8 @@ namespace minikv {
 constexpr int kSelThreads = 1024;      // 16 waves: one workgroup per unit
 constexpr int kSelBins = 2048;         // 11-bit digits
 constexpr int kSelLoads = 8;           // keys per thread in flight in a histogram pass
+constexpr int kSelSparse = 56;         // of a wave's 64 lanes with 8 keys each in such a step: matches in up to this
+                                       // many lanes count as few
 constexpr int kSelRangeLoads = 16;     // ... and in the first pass, which streams them from memory
 constexpr int kSelFixedWords = kSelBins + 2 * 16 + 16 + 16;   // hist, compaction totals (two buffers), scan totals, result
 constexpr int kSelMaxCached = 32768;   // most keys held in LDS
@@ -247,15 +249,34 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
 #pragma unroll
                 for (int e = 0; e < kSelLoads; ++e) kk[e] = gkey(kk[e]);
             }
-            bool match[kSelLoads], any = false;
+            bool match[kSelLoads];
+            unsigned long long lanes = 0;              // lanes that hold a token still sharing the prefix
+            const uint32_t span = hi < 32 ? 1u << hi : 0u;           // (hi < 32 here: the first digit is settled)
+            if (base + kSelThreads * kSelLoads <= N) { // (uniform) all but the last step: every slot is a token
 #pragma unroll
-            for (int e = 0; e < kSelLoads; ++e) {
-                match[e] = tok(e) < N && (kk[e] >> hi) == (prefix >> hi);
-                any |= match[e];
+                for (int e = 0; e < kSelLoads; ++e) {
+                    match[e] = (kk[e] ^ prefix) < span;
+                    lanes |= __ballot(match[e]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < kSelLoads; ++e) {
+                    match[e] = tok(e) < N && (kk[e] ^ prefix) < span;
+                    lanes |= __ballot(match[e]);
+                }
             }
-            if (__ballot(any) == 0) continue;          // after the first digit few tokens still share the prefix
+            if (lanes == 0) continue;                  // after the first digit few tokens still share the prefix
+            if (__popcll(lanes) <= kSelSparse) {
+                // ... and those few spread over the bins: one plain LDS add each costs a fraction of the
+                // ballots and shuffles of hist_add (5.4 -> 1.5 us for the second digit of 32768 keys)
 #pragma unroll
-            for (int e = 0; e < kSelLoads; ++e) hist_add(hist, match[e], (int)((kk[e] >> lo) & dm), lane);
+                for (int e = 0; e < kSelLoads; ++e)
+                    if (match[e]) atomicAdd(&hist[(kk[e] >> lo) & dm], 1);
+            } else {
+                // many: ties or a narrow range of scores, which would queue on few LDS addresses
+#pragma unroll
+                for (int e = 0; e < kSelLoads; ++e) hist_add(hist, match[e], (int)((kk[e] >> lo) & dm), lane);
+            }
         }
         __syncthreads();
         settle_digit(lo);
@@ -263,6 +284,60 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
 
     // ---- ordered compaction
     const uint32_t T = prefix;
+    if (cached) {
+        // Keys in LDS (at most kSelMaxCached of them, so at most 8 steps of 4096 tokens): every thread counts its 4
+        // consecutive tokens of every step first -- one wave scan per step, no barrier --, the 8 x 16 wave totals
+        // (in token order: step, then wave) are exchanged ONCE, and then every thread knows the slots of its
+        // tokens.  (One barrier per step, as in the loop below, made this phase 7 of the kernel's 26 us.)
+        constexpr int NS = kSelMaxCached / (kSelThreads * 4);
+        uint32_t *tots = (uint32_t *)hist;             // [NS][16] packed counts: larger | equal << 16 (each < 65536)
+        uint32_t before[NS];                           // counts of the lanes before this one in its wave, per step
+        const int nsteps = (N + kSelThreads * 4 - 1) / (kSelThreads * 4);
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+            before[st] = 0;
+            if (st < nsteps) {                         // (uniform)
+                const int start = st * kSelThreads * 4 + tid * 4;
+                uint32_t key[4];
+                load4(start, key);
+                uint32_t tot = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t g = start + j < N && key[j] > T, e = start + j < N && key[j] == T;
+                    tot += g | e << 16;
+                }
+                const uint32_t incl = (uint32_t)wave_scan_incl((int)tot);
+                before[st] = incl - tot;
+                if (lane == 63) tots[st * 16 + wave] = incl;
+            }
+        }
+        __syncthreads();
+        // prefix over the (step, wave) totals: lane l holds entries 2l and 2l + 1
+        const uint2 tv = lane < nsteps * 8 ? *(const uint2 *)&tots[2 * lane] : uint2{0u, 0u};
+        const uint32_t pair_incl = (uint32_t)wave_scan_incl((int)(tv.x + tv.y));
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+            if (st >= nsteps) break;
+            const int e = st * 16 + wv;                // this wave's entry of the step (uniform)
+            const uint32_t upto = (uint32_t)__builtin_amdgcn_readlane((int)pair_incl, e >> 1);   // through entry e | 1
+            const uint32_t x1 = (uint32_t)__builtin_amdgcn_readlane((int)tv.y, e >> 1), x0 = (uint32_t)__builtin_amdgcn_readlane((int)tv.x, e >> 1);
+            uint32_t excl = upto - x1 - ((e & 1) ? 0u : x0) + before[st];   // everything before this thread's 4 tokens
+            const int start = st * kSelThreads * 4 + tid * 4;
+            uint32_t key[4];
+            load4(start, key);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool g = start + j < N && key[j] > T, eq = start + j < N && key[j] == T;
+                const int g_before = (int)(excl & 0xFFFFu), e_before = (int)(excl >> 16);
+                // a larger key goes behind the larger ones and the kept equal ones before it; an equal one is kept
+                // while fewer than rem came before it, and then sits at that same place
+                const int slot = g_before + min(e_before, rem);
+                if ((g || (eq && e_before < rem)) && slot < k) row[slot] = start + j;   // (slot < k always holds; the test keeps a write in its row)
+                excl += (uint32_t)g | (uint32_t)eq << 16;
+            }
+        }
+        return;
+    }
     int gt_run = 0, eq_run = 0, buf = 0;
     for (int base = 0; base < N; base += kSelThreads * 4, buf ^= 1) {
         // 4 consecutive tokens per thread: their flags are summed in the thread, one scan per wave, and the 16
