@@ -12,6 +12,8 @@
 
 #include <hip/hip_fp16.h>
 
+#include <type_traits>
+
 namespace minikv {
 
 struct QuantArgs {
@@ -151,8 +153,11 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
         }
     }
     __syncthreads();
-    {
+    // (the two word-building passes exist twice: for a full block of BT tokens, where every index split below is a
+    // shift, and for the ragged last block of a unit, where they are divisions by run-time values)
+    auto k_words = [&](auto ntc) {
         // one thread per (token, word): the word's 16 channels are contiguous in the tile row and in par
+        const int nt = ntc;
         uint32_t *Kc = a.Kc + (size_t)u * kc_words(a.Tcap);
         const int npair = nt / 2;
         for (int wi = tid; wi < nt * 8; wi += 256) {
@@ -178,7 +183,8 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
             }
             Kc[k_word_index(t0 + i, w)] = acc.word();
         }
-    }
+    };
+    if (nt == BT) k_words(std::integral_constant<int, BT>()); else k_words(nt);
     __syncthreads();
 
     // ---------------- V: groups of G channels per token.  Statistics: one thread per (token, channel group),
@@ -206,8 +212,9 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
         par[gi] = float2{-zf, inv};
     }
     __syncthreads();
-    {
+    auto v_words = [&](auto ntc) {
         // one thread per (block of 16 tokens, channel pair): two words
+        const int nt = ntc;
         uint32_t *Vc = a.Vc + (size_t)u * vc_words(a.Tcap);
         const int nb = nt / 16;
         for (int wi = tid; wi < nb * (kD / 2); wi += 256) {
@@ -226,7 +233,8 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
             Vc[v_word_index(t0 / 16 + bl, 2 * cp)] = acc0.word();
             Vc[v_word_index(t0 / 16 + bl, 2 * cp + 1)] = acc1.word();
         }
-    }
+    };
+    if (nt == BT) v_words(std::integral_constant<int, BT>()); else v_words(nt);
 }
 
 // Runs after every workgroup of quantize_pack_kernel has finished (next kernel on the stream).
