@@ -156,6 +156,11 @@ int minikv_decode_attn(const minikv_shape *shape, const minikv_f16 *q, const min
  * out of range, as kv_append_residual leaves it), the new rows are written to their place in cache->Rk, Rv, and
  * the caller then uses r_len_next as the cache's r_len (swap the two pointers from step to step; no
  * synchronisation is involved).  kv_flush_residual and every other call take whichever array is current.
+ * Where the flush goes: Algorithm 1 quantizes a residual that has just become full BETWEEN the append and the
+ * attention (lines 10-15), which this entry point leaves no room for.  A loop built on it either runs the three
+ * separate calls on the step that fills the residual, or calls kv_flush_residual at the start of the next step
+ * (before that step's append): the cache ends up the same, and the one step that filled the residual has
+ * attended to those tokens still in fp16 instead of quantized.
  * Other arguments, checks and status codes as minikv_decode_attn; MINIKV_EINVAL when r_len_next is null,
  * misaligned or equal to cache->r_len. */
 int minikv_decode_step(const minikv_shape *shape, const minikv_f16 *q, const minikv_f16 *k_new, const minikv_f16 *v_new,
