@@ -126,7 +126,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
     int *hist = (int *)smem;                         // [kSelBins]
     int *sub_tot = hist + kSelBins;                  // [2][16]
     int *scan_tot = sub_tot + 2 * 16;                // [16]
-    int *found = scan_tot + 16;                      // [2] digit, kept count below it
+    int *found = scan_tot + 16;                      // [3] digit, kept count below it, keys in the digit's bin
     uint32_t *ck = smem + kSelFixedWords;            // [L] when cached
 
     const long u = blockIdx.x;
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
     // `rem` = how many tokens sharing them are still to be kept.  The FIRST digit is counted while the keys are
     // read from memory (and go to LDS when they fit): that pass waits for memory, the LDS counting rides along.
     uint32_t prefix = 0;
-    int rem = k;
+    int rem = k, in_bin = 0;                             // (in_bin: after the last digit, the keys equal to T)
     int hi = 32;
     // bins from the top down, two per thread; the thread whose pair crosses `rem` owns the digit
     auto settle_digit = [&](int lo) {
@@ -187,10 +187,12 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
             const bool upper = excl + c0 >= rem;
             found[0] = kSelBins - 1 - 2 * tid - (upper ? 0 : 1);
             found[1] = rem - (upper ? excl : excl + c0);
+            found[2] = upper ? c0 : c1;
         }
         __syncthreads();
         prefix |= (uint32_t)found[0] << lo;
         rem = found[1];
+        in_bin = found[2];
         hi = lo;
         __syncthreads();
     };
@@ -228,7 +230,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
     }
     __syncthreads();
     settle_digit(21);
-    while (hi > 0) {
+    // Further digits are needed only while the bin of the cut holds more keys than are kept from it.  Once ALL of
+    // them are kept (typically after the second digit: 32768 keys over four million bins leave the weakest kept
+    // key alone in its bin), T = the bin's lowest key does the same job, "kept" being key >= T.  (Only with the
+    // keys in LDS: the compaction that re-reads them from memory keeps the exact T.)
+    while (hi > 0 && !(cached && in_bin == rem)) {
         const int lo = max(hi - 11, 0);
         const uint32_t dm = (1u << (hi - lo)) - 1u;
         for (int b = tid; b < kSelBins; b += kSelThreads) hist[b] = 0;
@@ -293,6 +299,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
         uint32_t *tots = (uint32_t *)hist;             // [NS][16] packed counts: larger | equal << 16 (each < 65536)
         uint32_t before[NS];                           // counts of the lanes before this one in its wave, per step
         const int nsteps = (N + kSelThreads * 4 - 1) / (kSelThreads * 4);
+        // When every key of T's bin is kept (the usual case: no tie across the cut), "kept" is just key >= T and
+        // the bookkeeping of the equal ones falls away (3.7 instead of 5.9 us on 32768 tokens).
+        const bool all_equal_kept = in_bin == rem;     // (uniform)
 #pragma unroll
         for (int st = 0; st < NS; ++st) {
             before[st] = 0;
@@ -301,10 +310,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
                 uint32_t key[4];
                 load4(start, key);
                 uint32_t tot = 0;
+                if (all_equal_kept) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t g = start + j < N && key[j] > T, e = start + j < N && key[j] == T;
-                    tot += g | e << 16;
+                    for (int j = 0; j < 4; ++j) tot += (uint32_t)(start + j < N && key[j] >= T);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t g = start + j < N && key[j] > T, e = start + j < N && key[j] == T;
+                        tot += g | e << 16;
+                    }
                 }
                 const uint32_t incl = (uint32_t)wave_scan_incl((int)tot);
                 before[st] = incl - tot;
@@ -325,6 +339,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float *__rest
             const int start = st * kSelThreads * 4 + tid * 4;
             uint32_t key[4];
             load4(start, key);
+            if (all_equal_kept) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool g = start + j < N && key[j] >= T;
+                    if (g && (int)excl < k) row[excl] = start + j;   // (excl < k always holds; the test keeps a write in its row)
+                    excl += (uint32_t)g;
+                }
+                continue;
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const bool g = start + j < N && key[j] > T, eq = start + j < N && key[j] == T;
