@@ -162,3 +162,65 @@ def test_arguments_are_checked_on_the_host(g):
         api.minikv_decode_step(s, inp.q, k, k, c, c.r_len, g.sm_scale(), out)     # the same array for both lengths
     with pytest.raises(Exception):
         api.minikv_decode_step(s, inp.q, None, k, c, torch.zeros_like(c.r_len), g.sm_scale(), out)
+
+
+def test_two_fused_steps_captured_in_a_graph_and_replayed(g):
+    """The length arrays alternate from step to step, so a HIP graph holds TWO steps (lengths A -> B, then B -> A),
+    each with the flush in front.  The graph is replayed with new inputs in its static buffers, with eager work
+    and synchronisations between the replays; a twin cache runs the same steps eagerly as separate calls, and
+    every output and, at the end, the whole cache state agree bit for bit."""
+    from paper_2411_18077_amd import api
+    w = tiny(32, Rcap=32, keep=0.25)
+    inp = W.make_inputs(w, "cuda")
+    s, _ = g.shapes_for(w, (inp.Tcap + 2 * 32 + 127) // 128 * 128)
+    ca = g.gpu_build_cache(inp, s, r_len=29)               # the twin, driven eagerly with the separate calls
+    cb = g.gpu_build_cache(inp, s, r_len=29)
+    len_a, len_b = cb.r_len, torch.zeros_like(cb.r_len)
+    sm = g.sm_scale()
+    ks = [torch.zeros(w.units, w.D, dtype=torch.float16, device="cuda") for _ in range(2)]
+    vs = [torch.zeros_like(ks[0]) for _ in range(2)]
+    qs = [torch.zeros(w.B, w.Hq, w.D, dtype=torch.float16, device="cuda") for _ in range(2)]
+    outs = [torch.zeros_like(qs[0]) for _ in range(2)]
+    oa = torch.zeros_like(qs[0])
+    gen = torch.Generator(device="cuda").manual_seed(13)
+
+    def fresh():
+        for t in ks + vs + qs:
+            t.copy_(torch.randn(t.shape, generator=gen, device="cuda").to(torch.float16))
+
+    def two_steps():
+        api.kv_flush_residual(s, cb)                        # cb.r_len is len_a here
+        api.minikv_decode_step(s, qs[0], ks[0], vs[0], cb, len_b, sm, outs[0])
+        cb.swap_r_len(len_b)
+        api.kv_flush_residual(s, cb)
+        api.minikv_decode_step(s, qs[1], ks[1], vs[1], cb, len_a, sm, outs[1])
+        cb.swap_r_len(len_a)
+
+    def twin(i):
+        api.kv_flush_residual(s, ca)
+        api.kv_append_residual(s, ks[i], vs[i], ca)
+        api.minikv_decode_attn(s, qs[i], ca, sm, oa)
+        return oa.clone()
+
+    fresh()
+    two_steps()                                             # eagerly first (warm-up), then captured
+    want = [twin(0), twin(1)]
+    torch.cuda.synchronize()
+    assert all(torch.equal(outs[i].view(torch.int16), want[i].view(torch.int16)) for i in range(2))
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        two_steps()
+    for rep in range(20):                                   # 40 more tokens: crosses a flush
+        fresh()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = [twin(0), twin(1)]
+        torch.cuda.synchronize()
+        for i in range(2):
+            assert torch.equal(outs[i].view(torch.int16), want[i].view(torch.int16)), (rep, i)
+        (ks[0].float().sum() + qs[1].float().sum()).item()  # unrelated eager work between replays
+    assert torch.equal(ca.r_len, cb.r_len) and torch.equal(ca.q_len, cb.q_len)
+    for name in ("Kc", "Ks", "Kz", "Vc", "Vs", "Vz", "Rk", "Rv"):
+        assert torch.equal(ca.t[name], cb.t[name]), name
