@@ -849,17 +849,27 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             // hundreds of waves still ends with two short merges, and the first level runs while other
             // waves are still at work.
             constexpr int kSlotB = kNH * kPartialStride * 4, kHeadB = kPartialStride * 4;
-            const int lane8 = lane_p * 8;
-            float M[kNH], L[kNH], Oa[kNH], Ob[kNH];
-            // merges `count` partials, `stride` slots apart from slot `first`, into (M, L, Oa, Ob): lane s
-            // fetches (max, sum) of partial s, which gives every partial's weight; the output vectors
-            // (channels 2*lane, 2*lane+1 per lane) of up to 16 partials are requested in the same round trip
+            // The merging wave holds, per lane, 4 consecutive channels of two heads: lanes 0..31 of heads 0 and 2,
+            // lanes 32..63 of heads 1 and 3.  One 128-bit load per lane then fetches a partial's outputs of two heads,
+            // so the 16 partials of a sub-group are 32 + 4 loads: a wave can have 63 memory instructions outstanding,
+            // and with 64-bit loads (68 of them) the last ones went out only after the first had returned -- two
+            // round trips where this is one.
+            const int half_p = lane_p >> 5, c4 = lane_p & 31;
+            const unsigned lane_off = (unsigned)(half_p * kHeadB + 16 + c4 * 16);
+            float M[kNH], L[kNH];
+            f4 Oq[2];                                      // Oq[j]: channels 4*c4 .. 4*c4+3 of head 2*j + half_p
+            // merges `count` partials, `stride` slots apart from slot `first`, into (M, L, Oq): lane s fetches
+            // (max, sum) of partial s, which gives every partial's weight; the output vectors of up to 16
+            // partials are requested in the same round trip (device-scope loads: sc1)
             auto merge = [&](int first, int stride, int count) {
                 const char *const sbase = reinterpret_cast<const char *>(slot_ptr(a, first, 0));
-                const size_t step = (size_t)stride * kSlotB;
+                const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(sbase), 0, 0x7fffffff, 0x00020000);
+                const unsigned step = (unsigned)stride * kSlotB;
 #pragma unroll
-                for (int h = 0; h < kNH; h++) { M[h] = -1e30f; L[h] = 0.f; Oa[h] = 0.f; Ob[h] = 0.f; }
+                for (int h = 0; h < kNH; h++) { M[h] = -1e30f; L[h] = 0.f; }
+                Oq[0] = f4{0.f, 0.f, 0.f, 0.f}; Oq[1] = Oq[0];
                 constexpr int MB = 16;
+                constexpr int kSc1 = 16;                   // cache policy of the buffer load: device scope
 #pragma unroll 1
                 for (int base = 0; base < count; base += MB) {
                     const int cnt = min(MB, count - base);
@@ -873,48 +883,58 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                         ms[h] = on ? ml.x : -1e30f;        // partials that do not exist get weight 0 below
                         ls[h] = on ? ml.y : 0.f;
                     }
-                    float2 x[MB][kNH];
+                    f4 x[MB][2];
 #pragma unroll
                     for (int k = 0; k < MB; k++) {
-                        const char *const pk = sbase + (size_t)(base + min(k, cnt - 1)) * step;   // uniform
+                        const unsigned pk = (unsigned)(base + min(k, cnt - 1)) * step;   // uniform
 #pragma unroll
-                        for (int h = 0; h < kNH; h++)
-                            x[k][h] = ld_agent2(reinterpret_cast<const float *>(pk + h * kHeadB + 16 + lane8));
+                        for (int j = 0; j < 2; j++) {
+                            typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+                            const u4v v = __builtin_amdgcn_raw_buffer_load_b128(rs, lane_off, pk + (unsigned)(2 * j * kHeadB), kSc1);
+                            x[k][j] = __builtin_bit_cast(f4, v);
+                        }
                     }
 #pragma unroll
                     for (int h = 0; h < kNH; h++) cm[h] = ms[h];
                     wave_max64x4(cm);
                     float wgt[kNH], lw[kNH];
+                    float so2[2];
 #pragma unroll
                     for (int h = 0; h < kNH; h++) {
                         const float Mn = fmaxf(M[h], cm[h]);
                         const float so = fast_exp2(M[h] - Mn);
                         wgt[h] = fast_exp2(ms[h] - Mn);    // exactly 0 for ms = -1e30
                         lw[h] = ls[h] * wgt[h];
-                        L[h] *= so; Oa[h] *= so; Ob[h] *= so;
+                        L[h] *= so;
+                        if ((h & 1) == 0) so2[h >> 1] = so; else so2[h >> 1] = half_p ? so : so2[h >> 1];
                         M[h] = Mn;
                     }
+                    Oq[0] *= so2[0]; Oq[1] *= so2[1];
                     wave_sum64x4(lw);
 #pragma unroll
                     for (int h = 0; h < kNH; h++) L[h] += lw[h];
 #pragma unroll
                     for (int k = 0; k < MB; k++)
 #pragma unroll
-                        for (int h = 0; h < kNH; h++) {
-                            const float wl = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wgt[h]), k));
-                            Oa[h] += x[k][h].x * wl;
-                            Ob[h] += x[k][h].y * wl;
+                        for (int j = 0; j < 2; j++) {
+                            const float w0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wgt[2 * j]), k));
+                            const float w1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wgt[2 * j + 1]), k));
+                            const float wl = half_p ? w1 : w0;
+                            Oq[j] += x[k][j] * wl;
                         }
                 }
             };
             auto write_out = [&]() {
                 write_next_len();
 #pragma unroll
-                for (int h = 0; h < kNH; h++) {
+                for (int j = 0; j < 2; j++) {
+                    const int h = 2 * j + half_p;
                     if (h >= nheads) continue;
-                    const float inv = L[h] > 0.f ? 1.0f / L[h] : 0.f;
-                    const h2 r = {(_Float16)(Oa[h] * inv), (_Float16)(Ob[h] * inv)};
-                    *reinterpret_cast<uint32_t *>(a.out + (size_t)(bq0 + h) * kD + 2 * lane_p) = as_u32(r);
+                    const float Lh = half_p ? L[2 * j + 1] : L[2 * j];
+                    const float inv = Lh > 0.f ? 1.0f / Lh : 0.f;
+                    const h2 r0 = {(_Float16)(Oq[j][0] * inv), (_Float16)(Oq[j][1] * inv)};
+                    const h2 r1 = {(_Float16)(Oq[j][2] * inv), (_Float16)(Oq[j][3] * inv)};
+                    *reinterpret_cast<uint2 *>(a.out + (size_t)(bq0 + h) * kD + 4 * c4) = uint2{as_u32(r0), as_u32(r1)};
                 }
             };
             auto take_ticket = [&](int *counter) -> int {           // after this wave's stores are acknowledged
@@ -945,14 +965,17 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
                     write_out();
                 } else {
 #pragma unroll
-                    for (int h = 0; h < kNH; h++) {
+                    for (int j = 0; j < 2; j++) {
+                        const int h = 2 * j + half_p;
                         if (h < nheads) {
-                            float *pp = slot_ptr(a, slot1, h);
-                            st_agent(pp + 4 + 2 * lane, Oa[h]);
-                            st_agent(pp + 4 + 2 * lane + 1, Ob[h]);
-                            if (lane == 0) { st_agent(pp, M[h]); st_agent(pp + 1, L[h]); }
+                            float *pp = slot_ptr(a, slot1, h) + 4 + 4 * c4;
+#pragma unroll
+                            for (int e = 0; e < 4; e++) st_agent(pp + e, Oq[j][e]);
                         }
                     }
+#pragma unroll
+                    for (int h = 0; h < kNH; h++)
+                        if (h < nheads && lane == 0) { float *pp = slot_ptr(a, slot1, h); st_agent(pp, M[h]); st_agent(pp + 1, L[h]); }
                     const int old2 = take_ticket(a.cnt + up);
                     if (old2 == nsg - 1) {
                         merge(wf + 2 * up, 16, nsg);
