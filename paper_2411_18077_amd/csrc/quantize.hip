@@ -67,16 +67,32 @@ __device__ inline uint32_t quant_code(float x, float zf, float inv)
     return (uint32_t)(int)r;
 }
 
-template <int G>
-__device__ inline void load_rows(uint16_t *tile, const uint16_t *src, const QuantArgs &a, int u, int i0, int nt)
+// Where the rows this thread gathers start (in halfs from the tensor's base): the same for K and for V, so the
+// positions are read, clamped and turned into offsets once.  Thread t moves the 16-byte piece t % 16 of rows
+// t / 16, t / 16 + 16, ...
+template <int NR>
+__device__ __forceinline__ void row_offsets(size_t (&off)[NR], const QuantArgs &a, int u, int i0, int nt)
 {
     const int tid = threadIdx.x;
-    for (int r = tid >> 4; r < nt; r += 16) {
-        long row = a.idx ? (long)a.idx[(size_t)u * a.idx_stride + i0 + r] : (long)(i0 + r);
+#pragma unroll
+    for (int j = 0; j < NR; j++) {
+        const int r = (tid >> 4) + 16 * j;
+        long row = 0;
+        if (r < nt) row = a.idx ? (long)a.idx[(size_t)u * a.idx_stride + i0 + r] : (long)(i0 + r);
         row = row < 0 ? 0 : (row >= a.L ? a.L - 1 : row);
-        const uint4 *p = reinterpret_cast<const uint4 *>(src + ((size_t)u * a.L + row) * kD) + (tid & 15);
-        *reinterpret_cast<uint4 *>(tile + r * kRow + (tid & 15) * 8) = *p;
+        off[j] = ((size_t)u * a.L + row) * kD + (tid & 15) * 8;
     }
+}
+template <int NR>
+__device__ __forceinline__ void load_rows(uint16_t *tile, const uint16_t *src, const size_t (&off)[NR], int nt)
+{
+    const int tid = threadIdx.x;
+    uint4 x[NR];                                       // (rows past the block read row 0 of the unit and are not stored)
+#pragma unroll
+    for (int j = 0; j < NR; j++) x[j] = *reinterpret_cast<const uint4 *>(src + off[j]);
+#pragma unroll
+    for (int j = 0; j < NR; j++)
+        if ((tid >> 4) + 16 * j < nt) *reinterpret_cast<uint4 *>(tile + ((tid >> 4) + 16 * j) * kRow + (tid & 15) * 8) = x[j];
 }
 
 typedef _Float16 qh2 __attribute__((ext_vector_type(2)));
@@ -129,7 +145,9 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
 
     // ---------------- K: groups of G tokens per channel.  Statistics: one thread per (group, channel pair),
     // packed fp16 min / max (exact) down the G tokens.
-    load_rows<G>(tile, a.K, a, u, i0, nt);
+    size_t off[BT / 16];
+    row_offsets(off, a, u, i0, nt);
+    load_rows(tile, a.K, off, nt);
     __syncthreads();
     for (int gi = tid; gi < (nt / G) * (kD / 2); gi += 256) {
         const int g = gi / (kD / 2), cp = gi % (kD / 2);
@@ -155,7 +173,7 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
     __syncthreads();
     // (the two word-building passes exist twice: for a full block of BT tokens, where every index split below is a
     // shift, and for the ragged last block of a unit, where they are divisions by run-time values)
-    auto k_words = [&](auto ntc) {
+    auto k_words = [&a, tid, u, t0, one](auto ntc) {
         // one thread per (token, word): the word's 16 channels are contiguous in the tile row and in par
         const int nt = ntc;
         uint32_t *Kc = a.Kc + (size_t)u * kc_words(a.Tcap);
@@ -189,7 +207,7 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
 
     // ---------------- V: groups of G channels per token.  Statistics: one thread per (token, channel group),
     // the G values read 8 at a time.
-    load_rows<G>(tile, a.V, a, u, i0, nt);
+    load_rows(tile, a.V, off, nt);
     __syncthreads();
     for (int gi = tid; gi < nt * NCG; gi += 256) {
         const int i = gi / NCG, cg = gi % NCG;
@@ -212,7 +230,7 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(QuantArgs a)
         par[gi] = float2{-zf, inv};
     }
     __syncthreads();
-    auto v_words = [&](auto ntc) {
+    auto v_words = [&a, tid, u, t0, one](auto ntc) {
         // one thread per (block of 16 tokens, channel pair): two words
         const int nt = ntc;
         uint32_t *Vc = a.Vc + (size_t)u * vc_words(a.Tcap);
