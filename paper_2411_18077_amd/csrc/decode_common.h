@@ -22,10 +22,9 @@ struct DecArgs {
     int units, hsets;            // B*Hkv; sets of 4 query heads per KV head (1 or 2)
     int hs_shift;                // log2(hsets)
     uint32_t hkv_magic, hkv_shift;   // exact division by Hkv: see fast_div()
-    // the fused step (append + attend in one launch; all null / 0 otherwise): the new token's rows [B*Hkv][D],
-    // the residual buffers as writable pointers, and where the lengths after the append go
+    // the fused step (append + attend in one launch; all null / 0 otherwise): the new token's rows [B*Hkv][D]
+    // (filed in Rk, Rv, which the step may write) and where the lengths after the append go
     const uint16_t *k_new, *v_new;
-    uint16_t *Rk_w, *Rv_w;
     int32_t *r_len_out;
     int append;
 };

@@ -207,7 +207,7 @@ int launch_decode_parts(const minikv_shape &s, const minikv_f16 *q, const minikv
     a.Rk = c.Rk; a.Rv = c.Rv; a.q_len = c.q_len; a.r_len = c.r_len;
     a.out = out;
     a.append = ap.k_new != nullptr;
-    a.k_new = ap.k_new; a.v_new = ap.v_new; a.Rk_w = c.Rk; a.Rv_w = c.Rv; a.r_len_out = ap.r_len_out;
+    a.k_new = ap.k_new; a.v_new = ap.v_new; a.r_len_out = ap.r_len_out;
     a.first_slot = 0;
     a.cnt = cnt;
     a.cnt1 = cnt1;

@@ -213,7 +213,7 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
     int new_row = -1;
     const bool files_new = APPEND && (int)blockIdx.x < a.units && lane < 32;
     auto new_src = [&](int u) { return reinterpret_cast<const uint4 *>((lane < 16 ? a.k_new : a.v_new) + (size_t)u * kD) + (lane & 15); };
-    auto new_dst = [&](int u, int r) { return reinterpret_cast<uint4 *>((lane < 16 ? a.Rk_w : a.Rv_w) + ((size_t)u * a.Rcap + r) * kD) + (lane & 15); };
+    auto new_dst = [&](int u, int r) { return reinterpret_cast<uint4 *>(const_cast<uint16_t *>(lane < 16 ? a.Rk : a.Rv) + ((size_t)u * a.Rcap + r) * kD) + (lane & 15); };
     if (files_new) {
         new_row = a.r_len[blockIdx.x];
         new_piece = *new_src(blockIdx.x);
