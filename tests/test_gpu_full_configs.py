@@ -1,5 +1,5 @@
 """GPU parity at the full sizes of the five baseline configurations, in the launch configuration that
-bench.py times (default variant, one append + one decode call).  The oracle is evaluated on a seeded
+bench.py times (default variant; the step as one launch, minikv_decode_step, and as one append + one decode call).  The oracle is evaluated on a seeded
 sample of (batch, KV-head) units -- all of them for the two small configurations, 16 for the others plus
 the shortest and the longest unit of the ragged one -- and the packed cache of the sampled units must
 match the oracle's bit for bit."""
@@ -35,11 +35,18 @@ def test_full_config_sampled_units(g, name):
     cache.Rk.view(w.units, w.Rcap, w.D)[:, :r0].copy_(inp.Rk[:, :r0])
     cache.Rv.view(w.units, w.Rcap, w.D)[:, :r0].copy_(inp.Rv[:, :r0])
     cache.r_len.fill_(r0)
-    api.kv_append_residual(shape, inp.Rk[:, r0].contiguous(), inp.Rv[:, r0].contiguous(), cache)
+    k_new, v_new = inp.Rk[:, r0].contiguous(), inp.Rv[:, r0].contiguous()
+    # the step as bench.py times it -- append and attention in one launch (the lengths after the append go to
+    # r_next, the cache's own stay at r0) -- and then as the two calls; the two must agree bit for bit
+    out_step = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=torch.float16, device="cuda")
+    r_next = torch.full_like(cache.r_len, -7)
+    api.minikv_decode_step(shape, inp.q, k_new, v_new, cache, r_next, 1.0 / math.sqrt(w.D), out_step)
+    api.kv_append_residual(shape, k_new, v_new, cache)
     out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=torch.float16, device="cuda")
     api.minikv_decode_attn(shape, inp.q, cache, 1.0 / math.sqrt(w.D), out)
     torch.cuda.synchronize()
     assert torch.isfinite(out).all()
+    assert torch.equal(out.view(torch.int16), out_step.view(torch.int16)) and torch.equal(r_next, cache.r_len)
     assert api.minikv_diag_redo_count(shape, cache.workspace) == 0      # no unit needed the second attempt
 
     n_tok = inp.n_tok.cpu().numpy()
