@@ -471,13 +471,26 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
             // this launch)
             const int r_new = it.rn;                       // (a full or invalid buffer takes no token)
             const uint16_t *kn = APPEND ? a.k_new + (size_t)u * kD : nullptr, *vn = APPEND ? a.v_new + (size_t)u * kD : nullptr;
+            // (the rows are loaded as in the plain call; the item that holds the new row then loads it once more,
+            // from the caller's array, into the registers of the four-row step it belongs to: one wave-uniform branch
+            // per step instead of a select per row)
+            const bool has_new = APPEND && r_new >= t0 && r_new < t0 + 64;     // (uniform)
+            const int new_step = (r_new - t0) >> 2, new_sub = (r_new - t0) & 3;
             Words<64> g;
 #pragma unroll
             for (int i = 0; i < 16; i++) {
                 const int rr = t0 + 4 * i + rsub;
-                const uint16_t *src = rr == r_new ? kn : Rk + (size_t)(rr < R ? rr : 0) * kD;
+                const uint16_t *src = Rk + (size_t)(rr < R ? rr : 0) * kD;
                 const uint4 x = reinterpret_cast<const uint4 *>(src)[piece];
                 g.v[4 * i] = x.x; g.v[4 * i + 1] = x.y; g.v[4 * i + 2] = x.z; g.v[4 * i + 3] = x.w;
+            }
+            if (has_new) {
+#pragma unroll
+                for (int i = 0; i < 16; i++)
+                    if (i == new_step && rsub == new_sub) {
+                        const uint4 x = reinterpret_cast<const uint4 *>(kn)[piece];
+                        g.v[4 * i] = x.x; g.v[4 * i + 1] = x.y; g.v[4 * i + 2] = x.z; g.v[4 * i + 3] = x.w;
+                    }
             }
             // A operands of the scores: block b supplies k-steps b and b+16 (channels 4b.., 64+4b..) of head `row`
             h4 qa[2];
@@ -496,9 +509,17 @@ __global__ __launch_bounds__(64, G == 16 ? 1 : 2) void decode_stream_kernel(DecA
 #pragma unroll
             for (int i = 0; i < 16; i++) {
                 const int rr = t0 + 4 * i + rsub;
-                const uint16_t *src = rr == r_new ? vn : Rv + (size_t)(rr < R ? rr : 0) * kD;
+                const uint16_t *src = Rv + (size_t)(rr < R ? rr : 0) * kD;
                 const uint4 x = reinterpret_cast<const uint4 *>(src)[piece];
                 g.v[4 * i] = x.x; g.v[4 * i + 1] = x.y; g.v[4 * i + 2] = x.z; g.v[4 * i + 3] = x.w;
+            }
+            if (has_new) {
+#pragma unroll
+                for (int i = 0; i < 16; i++)
+                    if (i == new_step && rsub == new_sub) {
+                        const uint4 x = reinterpret_cast<const uint4 *>(vn)[piece];
+                        g.v[4 * i] = x.x; g.v[4 * i + 1] = x.y; g.v[4 * i + 2] = x.z; g.v[4 * i + 3] = x.w;
+                    }
             }
             __builtin_amdgcn_wave_barrier();
 
